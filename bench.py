@@ -1,0 +1,294 @@
+#!/usr/bin/env python3
+"""Benchmark of the ODC hot path on one MI355X.
+
+A "step" is one minibatch of the whole path over synthetic layer-shaped data that is already
+resident in HBM: every layer's accumulators are reset, then every logical worker w runs its
+M_w microbatches, and each microbatch gathers every layer (forward), then walks the layers in
+reverse gathering each again and pushing one scatter-accumulate contribution (backward) --
+the call sequence FSDP produces once its collectives are replaced by the ODC primitives
+(paper Sections 2.2 and 3).  Effective bytes follow the metric's rule: 4 B per element and
+gather, 10 B per element and contribution, 4 B per element and reset.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (ordered accumulate), timed
+with events on the launch stream inside the timed region; `cpu_baseline` is the CPU oracle
+timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+METRIC = "effective HBM GB/s (and % of peak) for gather + scatter-accumulate per layer"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b", choices=["tiny", "1.5b", "7b", "32b", "stress"])
+    ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket accumulate launches with events (roofline from a separate pass)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU-baseline sample time")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="measured HBM bytes per accumulate launch (from rocprofv3 --pmc runs)")
+    return ap.parse_args()
+
+
+def build_state(w, layers, torch, odc, inputs):
+    """Allocate and fill the resident buffers of `layers` parameter sets."""
+    dev = torch.device("cuda")
+    L = odc.Layout(w.R, w.numel)
+    arena, full_n = L.rank_arena_elems(), L.full_elems()
+    resident = min(layers, w.resident_layers)
+    sets = []
+    for s in range(resident):
+        flat = inputs.device_uniform_bf16(full_n, w.param_range[0], w.param_range[1],
+                                          1000 * w.seed + s, dev)
+        params = []
+        for r in range(w.R):
+            p = torch.empty(arena, dtype=torch.bfloat16, device=dev)
+            # contents only need the right distribution here; parity is the tests' job
+            lo = (r * arena) % max(full_n - arena, 1)
+            p.copy_(flat[lo:lo + arena])
+            params.append(p)
+        acc = [torch.empty(arena, dtype=torch.float32, device=dev) for _ in range(w.R)]
+        sets.append((odc.PtrArray(params), odc.PtrArray(acc)))
+        del flat
+    full = torch.empty(full_n, dtype=torch.bfloat16, device=dev)
+    pool = [inputs.device_normal_bf16(full_n, w.grad_sigma, 77 + k, dev) for k in range(4)]
+    return L, sets, full, pool
+
+
+def run_step(L, sets, full, pool, layers, M, odc, events=None):
+    """One minibatch.  Returns (gathers, contributions, resets) issued.
+
+    With fewer resident parameter sets than layers (the rotating window of the 32B-shaped
+    workload) layer l uses set l mod nset; the microbatch number handed to the ordered mode
+    is then made unique per (set, visit) so that the per-set order stays strictly ascending.
+    """
+    nset = len(sets)
+    visits = -(-layers // nset)
+    for l in range(layers):
+        L.reset_accum(sets[l % nset][1])
+    n_g = n_c = 0
+    k = 0
+    for w, mw in enumerate(M):
+        for m in range(mw):
+            for l in range(layers):                      # forward: gather every layer
+                L.gather(sets[l % nset][0], full)
+                n_g += 1
+            for l in reversed(range(layers)):            # backward: gather + contribution
+                L.gather(sets[l % nset][0], full)
+                n_g += 1
+                g = pool[k % len(pool)]
+                k += 1
+                slot = m * visits + (visits - 1 - l // nset)
+                if events is not None:
+                    e0, e1 = events.pair()
+                    e0.record()
+                    L.scatter_accumulate(g, sets[l % nset][1], w, slot, odc.ODC_ORDERED)
+                    e1.record()
+                else:
+                    L.scatter_accumulate(g, sets[l % nset][1], w, slot, odc.ODC_ORDERED)
+                n_c += 1
+    return n_g, n_c, layers
+
+
+class EventPool:
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = []
+
+    def pair(self):
+        p = (self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True))
+        self.pairs.append(p)
+        return p
+
+    def mean_ms(self):
+        if not self.pairs:
+            return None
+        return sum(a.elapsed_time(b) for a, b in self.pairs) / len(self.pairs)
+
+
+def time_kernel(fn, torch, reps=20, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in e:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in e)
+    return ts[len(ts) // 2], ts[0]
+
+
+def cpu_baseline(w, target_s):
+    """The CPU oracle as it stands, element-range-parallel over the host cores, on a bounded
+    sample: one parameter set -- reset, two gathers, then contributions until the time target."""
+    import numpy as np
+
+    import oracle
+    from paper_2601_19362_amd import inputs
+
+    cores = min(os.cpu_count() or 1, 16)
+    numel = list(w.numel)
+    if len(numel) == 1:
+        N, R = numel[0], w.R
+        S = oracle.shard_elems(N, R)
+        flat = inputs.uniform_bf16(N, w.param_range[0], w.param_range[1], seed=(w.seed, 900))
+        shards = oracle.make_shards(flat, R)
+        full = np.empty(N, dtype=np.uint16)
+        acc = [np.empty(S, dtype=np.float32) for _ in range(R)]
+        g = inputs.normal_bf16(N, w.grad_sigma, seed=(w.seed, 901))
+        ops = {"reset": lambda: oracle.reset(acc, N, nthreads=cores),
+               "gather": lambda: oracle.gather(shards, N, full, nthreads=cores),
+               "accum": lambda: oracle.accumulate(g, acc, N, nthreads=cores)}
+        total = N
+    else:
+        R = w.R
+        S = [-(-n // R) for n in numel]
+        so = np.concatenate([[0], np.cumsum([(s + 7) // 8 * 8 for s in S])[:-1]]).astype(np.int64)
+        fo = np.concatenate([[0], np.cumsum([(n + 7) // 8 * 8 for n in numel])[:-1]]).astype(np.int64)
+        arena, full_n = int(so[-1] + S[-1]), int(fo[-1] + numel[-1])
+        arenas = [inputs.uniform_bf16(arena, w.param_range[0], w.param_range[1], seed=(w.seed, 900, r))
+                  for r in range(R)]
+        full = np.empty(full_n, dtype=np.uint16)
+        acc = [np.empty(arena, dtype=np.float32) for _ in range(R)]
+        g = inputs.normal_bf16(full_n, w.grad_sigma, seed=(w.seed, 901))
+        ops = {"reset": lambda: oracle.reset_batched(acc, numel, so),
+               "gather": lambda: oracle.gather_batched(arenas, numel, so, fo, full),
+               "accum": lambda: oracle.accumulate_batched(g, acc, numel, so, fo)}
+        total = sum(numel)
+        cores = 1  # the batched oracle walks the tensors one after the other on one thread
+    t0 = time.perf_counter()
+    ops["reset"]()
+    ops["gather"]()
+    ops["gather"]()
+    nbytes = total * (4 + 2 * 4)
+    n_acc = 0
+    while n_acc < 2 or (time.perf_counter() - t0 < target_s and n_acc < 256):
+        ops["accum"]()
+        n_acc += 1
+        nbytes += total * 10
+    dt = time.perf_counter() - t0
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": (f"one parameter set of workload {w.name}: 1 reset + 2 gathers + {n_acc} "
+                       f"contributions (same gradient buffer reused), {dt:.1f} s of host time, "
+                       "same 4/10 B-per-element rule")}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU holds every logical rank's shard; "
+              "no collectives, no peer access); --gpus must be 1", file=sys.stderr)
+        return 2
+    import torch
+
+    from paper_2601_19362_amd import binding as odc
+    from paper_2601_19362_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    odc.lib()
+    for kv in args.tune:
+        k, v = kv.split("=")
+        odc.tune(k, int(v))
+
+    w = inputs.workload(args.workload)
+    layers = args.layers if args.layers > 0 else w.layers
+    M = inputs.microbatch_counts(w)
+    total = w.total_numel
+    L, sets, full, pool = build_state(w, layers, torch, odc, inputs)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        run_step(L, sets, full, pool, layers, M, odc)
+    torch.cuda.synchronize()
+
+    events = None if args.no_kernel_events else EventPool(torch)
+    t0 = time.perf_counter()
+    n_g = n_c = n_r = 0
+    for _ in range(args.steps):
+        a, b, c = run_step(L, sets, full, pool, layers, M, odc, events)
+        n_g, n_c, n_r = n_g + a, n_c + b, n_r + c
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    eff_bytes = total * (4 * n_g + 10 * n_c + 4 * n_r)
+    value = eff_bytes / dt / 1e9
+
+    # per-kernel figures
+    acc_ms = events.mean_ms() if events is not None else None
+    s0 = sets[0]
+    L.reset_accum(s0[1])  # also clears the ordered-mode history of this set
+    acc_med, acc_min = time_kernel(lambda: _accum_once(L, pool[0], s0[1], odc), torch)
+    gat_med, gat_min = time_kernel(lambda: L.gather(s0[0], full), torch)
+    rst_med, rst_min = time_kernel(lambda: L.reset_accum(s0[1]), torch)
+    nbytes_copy = (full.numel() * 2) // 16 * 16
+    scratch = torch.empty_like(full)
+    cp_med, cp_min = time_kernel(lambda: odc.probe_copy(scratch, full, nbytes_copy), torch)
+    del scratch
+    if acc_ms is None:
+        acc_ms = acc_med
+    achieved = 10 * total / (acc_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "config": {
+            "workload": (f"{w.name}: {layers} layer(s) x {w.T} flat param(s), {total} elements per layer, "
+                         f"R={w.R} logical ranks, {len(sets)} resident parameter set(s)"),
+            "microbatches_per_rank": M, "contributions_per_layer": sum(M),
+            "calls_per_step": {"gather": n_g // args.steps, "scatter_accumulate": n_c // args.steps,
+                               "reset": n_r // args.steps},
+            "bytes_rule": "4 B/elem/gather, 10 B/elem/contribution, 4 B/elem/reset",
+            "tune": args.tune,
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "scatter_accumulate (ordered)",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": args.traffic_bytes,
+            "avg_launch_ms": round(acc_ms, 4), "launches_timed": (len(events.pairs) if events else 0),
+            "algorithmic_bytes_per_launch": 10 * total,
+        },
+        "kernels": {
+            "scatter_accumulate_GBs": {"median": round(10 * total / acc_med / 1e6, 1), "best": round(10 * total / acc_min / 1e6, 1)},
+            "gather_GBs": {"median": round(4 * total / gat_med / 1e6, 1), "best": round(4 * total / gat_min / 1e6, 1)},
+            "reset_GBs": {"median": round(4 * total / rst_med / 1e6, 1), "best": round(4 * total / rst_min / 1e6, 1)},
+            "plain_copy_GBs": {"median": round(2 * nbytes_copy / cp_med / 1e6, 1), "best": round(2 * nbytes_copy / cp_min / 1e6, 1)},
+        },
+    }
+    if not args.no_cpu_baseline:
+        del sets, pool, full
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+_seq = [0]
+
+
+def _accum_once(L, g, acc, odc):
+    """One ordered contribution with a fresh (worker 0, microbatch k) slot."""
+    _seq[0] += 1
+    L.scatter_accumulate(g, acc, 0, _seq[0], odc.ODC_ORDERED)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,159 @@
+/*
+ * odc.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of
+ * On-Demand Communication (ODC), "Revisiting Parameter Server in LLM Post-Training".
+ *
+ * The paper (Section 3) replaces FSDP's per-layer collectives by two point-to-point
+ * primitives: gather (a worker fetches every owner's parameter shard and so obtains the
+ * full layer, in place of all-gather) and scatter-accumulate (a worker pushes slice r of
+ * its gradient to owner r, who adds it to its gradient shard, in place of reduce-scatter;
+ * Appendix B: the owner accumulates each contribution when it arrives).  Parameters and
+ * gradients are partitioned evenly over the R devices (Section 3.1) in FSDP's flat memory
+ * layout, and the accumulated gradients are read at the minibatch end (Section 3.2).
+ *
+ * In this library one GPU holds every logical rank's shard as a separate HBM buffer and
+ * executes all R owners' copies and accumulations itself: no peer access, no collectives.
+ *
+ * Conventions for every entry point
+ *   - All element data live in DEVICE memory owned by the caller.  Parameters and
+ *     gradient contributions are bf16 (raw 16-bit patterns); accumulators are IEEE-754
+ *     binary32.  Pointer arrays of length R ("[R] host") are HOST arrays of device
+ *     pointers; the library copies them during the call and keeps no reference.
+ *   - Every device base pointer (each shard, the full buffer, each accumulator shard, the
+ *     gradient) must be 16-byte aligned, else ODC_ERR_ALIGNMENT.  Interior boundaries
+ *     (r * S_t) may fall anywhere; that is the library's business.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Launch
+ *     calls only enqueue work on it and return: they never synchronise, allocate or free.
+ *     A call enqueues one kernel per group of up to 64 ranks, so exactly one kernel for
+ *     R <= 64, for any number of tensors T.
+ *   - Return value: ODC_OK (0) or a negative ODC_ERR_* code.  All argument errors are
+ *     detected on the host before anything is enqueued.  Nothing throws or aborts.
+ *   - Padding (shard slots whose flat index is >= numel) is never read into a result and
+ *     never written, by any call.
+ */
+#ifndef ODC_H
+#define ODC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct odc_layout odc_layout_t; /* opaque; owned by the library */
+
+#define ODC_OK 0
+#define ODC_ERR_INVALID_ARG (-1) /* null pointer, R/T/numel < 1, worker or microbatch out of range, bad flags */
+#define ODC_ERR_ALIGNMENT (-2)   /* a device base pointer is not 16-byte aligned */
+#define ODC_ERR_ORDER (-3)       /* ordered contribution not after the previous one for this accumulator set */
+#define ODC_ERR_OVERFLOW (-4)    /* sizes do not fit 63-bit element or byte counts */
+#define ODC_ERR_HIP (-5)         /* a HIP call failed; see odc_last_hip_error() */
+#define ODC_ERR_NO_DEVICE (-6)   /* layout was built host-only, or belongs to another device */
+#define ODC_ERR_NOMEM (-7)       /* host allocation failed */
+
+#define ODC_MAX_RANKS 4096
+
+/* odc_init_layout flags */
+#define ODC_LAYOUT_HOST_ONLY 1 /* integer layout only: no HIP call is made, launches are refused */
+
+/* odc_scatter_accumulate flags */
+#define ODC_ORDERED 0   /* plain read-add-write; bit-exact if issued in (worker, microbatch) order on one stream */
+#define ODC_UNORDERED 1 /* hardware float atomics; calls may be issued in any order and from several streams */
+
+/*
+ * Build the shard layout (Section 3.1: even partition over R owners; FSDP flat-param
+ * layout, Section 3) for T flat parameters of numel[t] >= 1 elements.
+ *   S_t          = ceil(numel[t] / R)                 slots of tensor t in every owner's shard
+ *   owner r      holds flat indices [r*S_t, (r+1)*S_t) of tensor t; indices >= numel[t] are padding
+ *   valid(t, r)  = clamp(numel[t] - r*S_t, 0, S_t)
+ * Buffer placement chosen by the library: inside an owner's buffer ("rank arena") and inside
+ * the full-length buffer, tensor t starts at a multiple of 8 elements (16 bytes of bf16)
+ * after tensor t-1; see odc_shard_offset / odc_full_offset.  For T = 1 both offsets are 0,
+ * a rank arena is exactly S_0 slots and the full buffer exactly numel[0] elements.
+ * Unless ODC_LAYOUT_HOST_ONLY is set, a descriptor table is allocated with hipMalloc on the
+ * current device (this call may synchronise); the layout can then be used on that device only.
+ * numel is a host array, copied.  *out receives the handle; free it with odc_free_layout.
+ */
+int odc_init_layout(int R, int T, const int64_t *numel, int flags, odc_layout_t **out);
+
+/* Release a layout and its device table (NULL is ignored).  Do not call while kernels that
+ * use the layout may still be running. */
+void odc_free_layout(odc_layout_t *layout);
+
+/* Layout queries (host, pure).  Return -1 for a NULL layout or an index out of range. */
+int odc_num_ranks(const odc_layout_t *layout);
+int odc_num_tensors(const odc_layout_t *layout);
+int64_t odc_numel(const odc_layout_t *layout, int t);
+int64_t odc_shard_elems(const odc_layout_t *layout, int t);        /* S_t */
+int64_t odc_valid_elems(const odc_layout_t *layout, int t, int r); /* valid(t, r) */
+int64_t odc_rank_arena_elems(const odc_layout_t *layout);          /* elements each owner buffer must hold */
+int64_t odc_full_elems(const odc_layout_t *layout);                /* elements the full-length buffer must hold */
+int64_t odc_shard_offset(const odc_layout_t *layout, int t);       /* start of tensor t inside a rank arena */
+int64_t odc_full_offset(const odc_layout_t *layout, int t);        /* start of tensor t inside the full buffer */
+
+/*
+ * Gather (Section 3; Appendix B: each rank pulls the shards of all ranks):
+ *   full_out[full_off_t + r*S_t + i] = param_shards[r][shard_off_t + i]   for i < valid(t, r)
+ * bits copied unchanged.
+ *   param_shards  [R] host array of device pointers, bf16, each >= odc_rank_arena_elems elements, read only
+ *   full_out      device, bf16, >= odc_full_elems elements; only valid elements are written
+ * Algorithmic HBM traffic: 4 bytes per valid element.
+ */
+int odc_gather(const odc_layout_t *layout, const void *const *param_shards, void *full_out,
+               void *stream);
+
+/*
+ * One scatter-accumulate contribution (Section 3; Appendix B; Section 2.1 with w_m = 1):
+ * worker `worker`'s gradient for its microbatch `microbatch`, laid out like the full
+ * buffer, is cut into R slices and slice r is added into owner r's accumulator:
+ *   accum_shards[r][shard_off_t + i] += widen(grad_full[full_off_t + r*S_t + i])   for i < valid(t, r)
+ * widen(bf16) is exact; the sum is one binary32 addition, round-to-nearest-even, subnormals kept.
+ *   grad_full     device, bf16, >= odc_full_elems elements, read only
+ *   accum_shards  [R] host array of device pointers, binary32, each >= odc_rank_arena_elems elements
+ *   worker        in [0, R); microbatch >= 0
+ *   flags         ODC_ORDERED: the result is bit-identical to the sequential sum in
+ *                 (worker, microbatch) lexicographic order provided the caller issues the
+ *                 contributions of one accumulator set in that order on one stream.  The library
+ *                 remembers the last (worker, microbatch) per (layout, accum_shards[0]) and
+ *                 returns ODC_ERR_ORDER, enqueuing nothing, if a call is not strictly later;
+ *                 odc_reset_accum forgets it.  Two ordered calls on the same accumulators
+ *                 running concurrently on different streams race (caller error).
+ *                 ODC_UNORDERED: each element is added with a device-scope float atomic add
+ *                 (no order check); concurrent calls on several streams are safe, the result
+ *                 depends on arrival order within the usual binary32 summation error, and the
+ *                 atomic unit may flush subnormal values to zero.
+ * Algorithmic HBM traffic: 10 bytes per valid element (2 + 4 read, 4 written).
+ */
+int odc_scatter_accumulate(const odc_layout_t *layout, const void *grad_full,
+                           void *const *accum_shards, int worker, int microbatch, int flags,
+                           void *stream);
+
+/*
+ * Start of a minibatch (Section 3.2: accumulated gradients are retrieved at the minibatch
+ * end, so accumulators are cleared before the next one): every valid accumulator element
+ * becomes +0.0f.  Also clears the ordered-mode history of this accumulator set.
+ * Algorithmic HBM traffic: 4 bytes per valid element.
+ */
+int odc_reset_accum(const odc_layout_t *layout, void *const *accum_shards, void *stream);
+
+/* Text for an ODC_* code (static string, never NULL). */
+const char *odc_strerror(int code);
+
+/* hipError_t of the most recent failing HIP call on this host thread (0 if none). */
+int odc_last_hip_error(void);
+
+/*
+ * Diagnostics, not part of the method.
+ * odc_probe_copy: plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned) on `stream`: a kernel of known traffic used to calibrate
+ * hardware counters and to measure this GPU's copy ceiling next to the ODC kernels.
+ * odc_tune: set a launch knob by name for all later calls of this process ("gather_unroll",
+ * "accum_unroll", "nontemporal", "max_grid_x", "accum_width"); returns ODC_ERR_INVALID_ARG
+ * for an unknown name or a value out of range.  Results never depend on the knobs.
+ */
+int odc_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
+int odc_tune(const char *knob, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ODC_H */

@@ -1,0 +1,245 @@
+"""ctypes binding of libodc.so: same names as the C ABI in include/odc.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; torch is used
+by callers for device memory and streams.  There is no fallback: if the built library is
+missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libodc.so")
+
+ODC_OK = 0
+ODC_ERR_INVALID_ARG = -1
+ODC_ERR_ALIGNMENT = -2
+ODC_ERR_ORDER = -3
+ODC_ERR_OVERFLOW = -4
+ODC_ERR_HIP = -5
+ODC_ERR_NO_DEVICE = -6
+ODC_ERR_NOMEM = -7
+ODC_MAX_RANKS = 4096
+ODC_LAYOUT_HOST_ONLY = 1
+ODC_ORDERED = 0
+ODC_UNORDERED = 1
+
+EXPORTS = (
+    "odc_init_layout", "odc_free_layout", "odc_num_ranks", "odc_num_tensors", "odc_numel",
+    "odc_shard_elems", "odc_valid_elems", "odc_rank_arena_elems", "odc_full_elems",
+    "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
+    "odc_reset_accum", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+)
+
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_vp = ctypes.c_void_p
+_lib = None
+
+
+class OdcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = strerror(code)
+        if code == ODC_ERR_HIP:
+            detail += f" [hipError {lib().odc_last_hip_error()}]"
+        super().__init__(f"{where}: {detail} ({code})")
+
+
+def lib():
+    """Load the built library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it first (python -m paper_2601_19362_amd.build); "
+                "there is no CPU fallback")
+        # torch ships its own HIP runtime; import it first so that the dynamic loader binds
+        # this library to that same runtime (one runtime per process: streams and device
+        # pointers made by torch must be valid in the launches made here).
+        import torch  # noqa: F401
+
+        L = ctypes.CDLL(LIB_PATH)
+        L.odc_init_layout.restype = _int
+        L.odc_init_layout.argtypes = [_int, _int, ctypes.POINTER(_i64), _int, ctypes.POINTER(_vp)]
+        L.odc_free_layout.restype = None
+        L.odc_free_layout.argtypes = [_vp]
+        for name in ("odc_num_ranks", "odc_num_tensors"):
+            getattr(L, name).restype = _int
+            getattr(L, name).argtypes = [_vp]
+        for name in ("odc_numel", "odc_shard_elems", "odc_shard_offset", "odc_full_offset"):
+            getattr(L, name).restype = _i64
+            getattr(L, name).argtypes = [_vp, _int]
+        L.odc_valid_elems.restype = _i64
+        L.odc_valid_elems.argtypes = [_vp, _int, _int]
+        for name in ("odc_rank_arena_elems", "odc_full_elems"):
+            getattr(L, name).restype = _i64
+            getattr(L, name).argtypes = [_vp]
+        L.odc_gather.restype = _int
+        L.odc_gather.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp]
+        L.odc_scatter_accumulate.restype = _int
+        L.odc_scatter_accumulate.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _int, _int, _int, _vp]
+        L.odc_reset_accum.restype = _int
+        L.odc_reset_accum.argtypes = [_vp, ctypes.POINTER(_vp), _vp]
+        L.odc_strerror.restype = ctypes.c_char_p
+        L.odc_strerror.argtypes = [_int]
+        L.odc_last_hip_error.restype = _int
+        L.odc_last_hip_error.argtypes = []
+        L.odc_probe_copy.restype = _int
+        L.odc_probe_copy.argtypes = [_vp, _vp, _i64, _vp]
+        L.odc_tune.restype = _int
+        L.odc_tune.argtypes = [ctypes.c_char_p, _int]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().odc_strerror(int(code)).decode()
+
+
+def _ptr(x) -> Optional[int]:
+    """Device (or raw) address of a torch tensor, an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch stream object, a raw handle, or torch's current stream."""
+    if stream is None:
+        import torch
+
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+class PtrArray:
+    """A host array of R device pointers, built once and reused across calls."""
+
+    def __init__(self, tensors: Sequence):
+        self.n = len(tensors)
+        self.array = (_vp * self.n)(*[_ptr(t) for t in tensors])
+        self.keepalive = list(tensors)
+
+
+def _ptr_array(x, R: int):
+    if isinstance(x, PtrArray):
+        if x.n != R:
+            raise ValueError(f"expected {R} pointers, got {x.n}")
+        return x.array
+    if x is None:
+        return None
+    if len(x) != R:
+        raise ValueError(f"expected {R} pointers, got {len(x)}")
+    return (_vp * R)(*[_ptr(t) for t in x])
+
+
+class Layout:
+    """Owner of an odc_layout_t handle.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, R: int, numel: Sequence[int], host_only: bool = False):
+        T = len(numel)
+        arr = (_i64 * max(T, 1))(*[int(n) for n in numel])
+        handle = _vp()
+        flags = ODC_LAYOUT_HOST_ONLY if host_only else 0
+        rc = lib().odc_init_layout(int(R), T, arr, flags, ctypes.byref(handle))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_init_layout")
+        self._h = handle
+        self.R = int(R)
+        self.T = T
+
+    # -- lifetime
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().odc_free_layout(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    # -- queries
+    def num_ranks(self) -> int:
+        return lib().odc_num_ranks(self._h)
+
+    def num_tensors(self) -> int:
+        return lib().odc_num_tensors(self._h)
+
+    def numel(self, t: int = 0) -> int:
+        return lib().odc_numel(self._h, t)
+
+    def shard_elems(self, t: int = 0) -> int:
+        return lib().odc_shard_elems(self._h, t)
+
+    def valid_elems(self, t: int, r: int) -> int:
+        return lib().odc_valid_elems(self._h, t, r)
+
+    def rank_arena_elems(self) -> int:
+        return lib().odc_rank_arena_elems(self._h)
+
+    def full_elems(self) -> int:
+        return lib().odc_full_elems(self._h)
+
+    def shard_offset(self, t: int) -> int:
+        return lib().odc_shard_offset(self._h, t)
+
+    def full_offset(self, t: int) -> int:
+        return lib().odc_full_offset(self._h, t)
+
+    # -- launches (raise OdcError on a non-zero code)
+    def gather(self, param_shards, full_out, stream=None) -> None:
+        rc = gather_rc(self, param_shards, full_out, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_gather")
+
+    def scatter_accumulate(self, grad_full, accum_shards, worker: int, microbatch: int,
+                           flags: int = ODC_ORDERED, stream=None) -> None:
+        rc = scatter_accumulate_rc(self, grad_full, accum_shards, worker, microbatch, flags, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_scatter_accumulate")
+
+    def reset_accum(self, accum_shards, stream=None) -> None:
+        rc = reset_accum_rc(self, accum_shards, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_reset_accum")
+
+
+# Raw-code variants (used by tests of the error paths; a stream of 0 skips the torch lookup).
+def gather_rc(layout: Layout, param_shards, full_out, stream=None) -> int:
+    return lib().odc_gather(layout.handle, _ptr_array(param_shards, layout.R), _ptr(full_out),
+                            _stream(stream))
+
+
+def scatter_accumulate_rc(layout: Layout, grad_full, accum_shards, worker: int, microbatch: int,
+                          flags: int = ODC_ORDERED, stream=None) -> int:
+    return lib().odc_scatter_accumulate(layout.handle, _ptr(grad_full),
+                                        _ptr_array(accum_shards, layout.R), int(worker),
+                                        int(microbatch), int(flags), _stream(stream))
+
+
+def reset_accum_rc(layout: Layout, accum_shards, stream=None) -> int:
+    return lib().odc_reset_accum(layout.handle, _ptr_array(accum_shards, layout.R), _stream(stream))
+
+
+def probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    rc = lib().odc_probe_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream))
+    if rc != ODC_OK:
+        raise OdcError(rc, "odc_probe_copy")
+
+
+def tune(knob: str, value: int) -> None:
+    rc = lib().odc_tune(knob.encode(), int(value))
+    if rc != ODC_OK:
+        raise OdcError(rc, f"odc_tune({knob}={value})")

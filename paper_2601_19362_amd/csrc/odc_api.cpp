@@ -1,0 +1,283 @@
+// C ABI of the ODC hot-path library: argument validation, ordered-mode bookkeeping and
+// kernel launches.  All argument errors are reported before anything is enqueued.
+#include "../../include/odc.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+
+#include "odc_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = static_cast<int>(e);
+    return ODC_ERR_HIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by the three launch calls.  On success *ptrs_ok is the validated array.
+int check_launchable(const odc_layout_t *L, const void *const *ptrs)
+{
+    if (!L || !ptrs) return ODC_ERR_INVALID_ARG;
+    for (int r = 0; r < L->host.R; ++r)
+        if (!ptrs[r]) return ODC_ERR_INVALID_ARG;
+    for (int r = 0; r < L->host.R; ++r)
+        if (!aligned16(ptrs[r])) return ODC_ERR_ALIGNMENT;
+    return ODC_OK;
+}
+
+int check_device(const odc_layout_t *L)
+{
+    if (L->host_only) return ODC_ERR_NO_DEVICE;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev != L->device) return ODC_ERR_NO_DEVICE;
+    return ODC_OK;
+}
+
+int upload_table(odc_layout_t *L)
+{
+    hipError_t e = hipGetDevice(&L->device);
+    if (e != hipSuccess) return hip_fail(e);
+    if (L->host.T == 1) return ODC_OK;  // flat kernels need no table
+    const odc::HostLayout &H = L->host;
+    const size_t T = static_cast<size_t>(H.T);
+    const size_t off_bytes = T * sizeof(int64_t);
+    const size_t desc_bytes = T * sizeof(odc::TensorDesc);
+    const size_t chunk_bytes = H.chunk_first.size() * sizeof(int32_t);
+    const size_t total = off_bytes + desc_bytes + chunk_bytes;
+    char *staging = new (std::nothrow) char[total];
+    if (!staging) return ODC_ERR_NOMEM;
+    int64_t *offs = reinterpret_cast<int64_t *>(staging);
+    for (size_t t = 0; t < T; ++t) offs[t] = H.desc[t].shard_off;
+    std::memcpy(staging + off_bytes, H.desc.data(), desc_bytes);
+    std::memcpy(staging + off_bytes + desc_bytes, H.chunk_first.data(), chunk_bytes);
+    e = hipMalloc(&L->d_blob, total);
+    if (e == hipSuccess) e = hipMemcpy(L->d_blob, staging, total, hipMemcpyHostToDevice);
+    delete[] staging;
+    if (e != hipSuccess) {
+        if (L->d_blob) (void)hipFree(L->d_blob);
+        L->d_blob = nullptr;
+        return hip_fail(e);
+    }
+    char *d = static_cast<char *>(L->d_blob);
+    L->table.shard_off = reinterpret_cast<const int64_t *>(d);
+    L->table.desc = reinterpret_cast<const odc::TensorDesc *>(d + off_bytes);
+    L->table.chunk_first = reinterpret_cast<const int32_t *>(d + off_bytes + desc_bytes);
+    L->table.arena_elems = H.arena_elems;
+    L->table.T = H.T;
+    return ODC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int odc_init_layout(int R, int T, const int64_t *numel, int flags, odc_layout_t **out)
+{
+    if (!out) return ODC_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (flags & ~ODC_LAYOUT_HOST_ONLY) return ODC_ERR_INVALID_ARG;
+    odc_layout_t *L = new (std::nothrow) odc_layout_t;
+    if (!L) return ODC_ERR_NOMEM;
+    int rc = odc::build_host_layout(R, T, numel, &L->host);
+    if (rc == ODC_OK && !(flags & ODC_LAYOUT_HOST_ONLY)) {
+        L->host_only = false;
+        rc = upload_table(L);
+    }
+    if (rc != ODC_OK) {
+        delete L;
+        return rc;
+    }
+    *out = L;
+    return ODC_OK;
+}
+
+void odc_free_layout(odc_layout_t *layout)
+{
+    if (!layout) return;
+    if (layout->d_blob) (void)hipFree(layout->d_blob);
+    delete layout;
+}
+
+int odc_num_ranks(const odc_layout_t *L) { return L ? L->host.R : -1; }
+int odc_num_tensors(const odc_layout_t *L) { return L ? L->host.T : -1; }
+
+#define ODC_TENSOR_OR_FAIL(L, t) \
+    if (!(L) || (t) < 0 || (t) >= (L)->host.T) return -1
+
+int64_t odc_numel(const odc_layout_t *L, int t)
+{
+    ODC_TENSOR_OR_FAIL(L, t);
+    return L->host.desc[static_cast<size_t>(t)].numel;
+}
+
+int64_t odc_shard_elems(const odc_layout_t *L, int t)
+{
+    ODC_TENSOR_OR_FAIL(L, t);
+    return L->host.desc[static_cast<size_t>(t)].S;
+}
+
+int64_t odc_valid_elems(const odc_layout_t *L, int t, int r)
+{
+    ODC_TENSOR_OR_FAIL(L, t);
+    if (r < 0 || r >= L->host.R) return -1;
+    return odc::valid_elems(L->host.desc[static_cast<size_t>(t)], r);
+}
+
+int64_t odc_rank_arena_elems(const odc_layout_t *L) { return L ? L->host.arena_elems : -1; }
+int64_t odc_full_elems(const odc_layout_t *L) { return L ? L->host.full_elems : -1; }
+
+int64_t odc_shard_offset(const odc_layout_t *L, int t)
+{
+    ODC_TENSOR_OR_FAIL(L, t);
+    return L->host.desc[static_cast<size_t>(t)].shard_off;
+}
+
+int64_t odc_full_offset(const odc_layout_t *L, int t)
+{
+    ODC_TENSOR_OR_FAIL(L, t);
+    return L->host.desc[static_cast<size_t>(t)].full_off;
+}
+
+int odc_gather(const odc_layout_t *L, const void *const *param_shards, void *full_out, void *stream)
+{
+    int rc = check_launchable(L, param_shards);
+    if (rc != ODC_OK) return rc;
+    if (!full_out) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(full_out)) return ODC_ERR_ALIGNMENT;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_gather_flat(param_shards + r0, r0, nr, full_out, H.desc[0].S,
+                                        H.desc[0].numel, stream);
+        else
+            e = odc::launch_gather_batched(L->table, param_shards + r0, r0, nr, full_out, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    return ODC_OK;
+}
+
+int odc_scatter_accumulate(const odc_layout_t *L, const void *grad_full, void *const *accum_shards,
+                           int worker, int microbatch, int flags, void *stream)
+{
+    int rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (!grad_full) return ODC_ERR_INVALID_ARG;
+    if (flags != ODC_ORDERED && flags != ODC_UNORDERED) return ODC_ERR_INVALID_ARG;
+    if (worker < 0 || worker >= L->host.R || microbatch < 0) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(grad_full)) return ODC_ERR_ALIGNMENT;
+
+    const bool atomic = flags == ODC_UNORDERED;
+    odc_layout_t *M = const_cast<odc_layout_t *>(L);
+    // Ordered mode: strictly ascending (worker, microbatch) per accumulator set.  The lock
+    // is held until the kernels are enqueued so that history and stream order agree.
+    std::unique_lock<std::mutex> lock(M->mu, std::defer_lock);
+    const std::pair<int, int> now{worker, microbatch};
+    std::pair<int, int> *slot = nullptr;
+    bool inserted = false;
+    if (!atomic) {
+        lock.lock();
+        try {
+            auto res = M->last.try_emplace(accum_shards[0], -1, -1);
+            slot = &res.first->second;
+            inserted = res.second;
+        } catch (...) {
+            return ODC_ERR_NOMEM;
+        }
+        if (!(*slot < now)) return ODC_ERR_ORDER;
+    }
+    rc = check_device(L);
+    const odc::HostLayout &H = L->host;
+    for (int r0 = 0; rc == ODC_OK && r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_accum_flat(accum_shards + r0, r0, nr, grad_full, H.desc[0].S,
+                                       H.desc[0].numel, atomic, stream);
+        else
+            e = odc::launch_accum_batched(L->table, accum_shards + r0, r0, nr, grad_full, atomic,
+                                          stream);
+        if (e != 0) rc = hip_fail(static_cast<hipError_t>(e));
+        else if (slot) {
+            *slot = now;  // something was enqueued: this contribution counts as issued
+            inserted = false;
+        }
+    }
+    if (inserted) M->last.erase(accum_shards[0]);  // nothing was enqueued
+    return rc;
+}
+
+int odc_reset_accum(const odc_layout_t *L, void *const *accum_shards, void *stream)
+{
+    int rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_reset_flat(accum_shards + r0, r0, nr, H.desc[0].S, H.desc[0].numel, stream);
+        else
+            e = odc::launch_reset_batched(L->table, accum_shards + r0, r0, nr, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    odc_layout_t *M = const_cast<odc_layout_t *>(L);
+    std::lock_guard<std::mutex> lock(M->mu);
+    M->last.erase(accum_shards[0]);
+    return ODC_OK;
+}
+
+const char *odc_strerror(int code)
+{
+    switch (code) {
+        case ODC_OK: return "success";
+        case ODC_ERR_INVALID_ARG: return "invalid argument";
+        case ODC_ERR_ALIGNMENT: return "device base pointer is not 16-byte aligned";
+        case ODC_ERR_ORDER: return "ordered contribution is not after the previous (worker, microbatch)";
+        case ODC_ERR_OVERFLOW: return "size arithmetic overflows 64 bits";
+        case ODC_ERR_HIP: return "HIP call failed (see odc_last_hip_error)";
+        case ODC_ERR_NO_DEVICE: return "layout is host-only or belongs to another device";
+        case ODC_ERR_NOMEM: return "host allocation failed";
+        default: return "unknown ODC error code";
+    }
+}
+
+int odc_last_hip_error(void) { return g_last_hip_error; }
+
+int odc_probe_copy(void *dst, const void *src, int64_t bytes, void *stream)
+{
+    if (!dst || !src || bytes < 0 || (bytes & 15)) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(dst) || !aligned16(src)) return ODC_ERR_ALIGNMENT;
+    const int e = odc::launch_probe_copy(dst, src, bytes, stream);
+    return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
+}
+
+int odc_tune(const char *knob, int value)
+{
+    if (!knob) return ODC_ERR_INVALID_ARG;
+    odc::Tuning &t = odc::tuning();
+    const bool unroll_ok = value == 1 || value == 2 || value == 4 || value == 8;
+    if (!std::strcmp(knob, "gather_unroll") && unroll_ok) t.gather_unroll = value;
+    else if (!std::strcmp(knob, "accum_unroll") && unroll_ok) t.accum_unroll = value;
+    else if (!std::strcmp(knob, "accum_width") && (value == 4 || value == 8)) t.accum_width = value;
+    else if (!std::strcmp(knob, "nontemporal") && (value == 0 || value == 1)) t.nontemporal = value;
+    else if (!std::strcmp(knob, "max_grid_x") && value >= 0) t.max_grid_x = value;
+    else return ODC_ERR_INVALID_ARG;
+    return ODC_OK;
+}
+
+}  // extern "C"

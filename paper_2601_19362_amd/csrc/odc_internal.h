@@ -1,0 +1,107 @@
+// Internal interfaces between the host layout code, the C-ABI layer and the gfx950 kernels.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <unordered_map>
+#include <utility>
+#include <vector>
+
+namespace odc {
+
+// Ranks served by one kernel launch: their base pointers travel by value in the kernel
+// arguments (64 * 8 bytes), so no per-call device table or host-to-device copy is needed.
+constexpr int kRanksPerLaunch = 64;
+// Every tensor starts at a multiple of this many elements inside a rank arena and inside
+// the full buffer: 16 bytes of bf16, 32 bytes of binary32.
+constexpr int64_t kAlignElems = 8;
+// Rank-arena elements per entry of the coarse tensor-lookup index (power of two).
+constexpr int kChunkShift = 11;
+
+// Per-tensor record read by the batched kernels.
+struct TensorDesc {
+    int64_t shard_off;  // start inside every rank arena (elements)
+    int64_t full_off;   // start inside the full buffer (elements)
+    int64_t numel;      // N_t
+    int64_t S;          // ceil(N_t / R)
+};
+
+// Device-side lookup data of a multi-tensor layout (all pointers are device pointers).
+struct BatchTable {
+    const int64_t *shard_off;    // [T + 1], ascending; shard_off[T] = arena_elems rounded up
+    const TensorDesc *desc;      // [T]
+    const int32_t *chunk_first;  // [n_chunks + 1]: last tensor starting at or before chunk start
+    int64_t arena_elems;
+    int32_t T;
+};
+
+struct HostLayout {
+    int R = 0;
+    int T = 0;
+    std::vector<TensorDesc> desc;
+    int64_t arena_elems = 0;
+    int64_t full_elems = 0;
+    int64_t total_numel = 0;
+    std::vector<int32_t> chunk_first;  // built for T > 1
+};
+
+// Pure integer layout construction (Section 3.1 even partition, tail padding).
+// Returns an ODC_* code; never touches the GPU.
+int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out);
+
+inline int64_t valid_elems(const TensorDesc &d, int r)
+{
+    int64_t v = d.numel - static_cast<int64_t>(r) * d.S;
+    if (v < 0) v = 0;
+    if (v > d.S) v = d.S;
+    return v;
+}
+
+// Workgroups along x for `items` work items at `per_block` items per workgroup pass.  The
+// kernels loop over tiles, so a capped grid is still complete.
+inline unsigned grid_x_for(int64_t items, int per_block, int cap)
+{
+    int64_t tiles = (items + per_block - 1) / per_block;
+    if (tiles < 1) tiles = 1;
+    if (cap > 0 && tiles > cap) tiles = cap;
+    if (tiles > 0x7FFFFFFF) tiles = 0x7FFFFFFF;
+    return static_cast<unsigned>(tiles);
+}
+
+// Launch knobs (process-wide, diagnostics only).
+struct Tuning {
+    int gather_unroll = 4;   // 16-byte vectors per thread in the gather kernels (1, 2, 4, 8)
+    int accum_unroll = 4;    // accumulator vectors per thread (1, 2, 4, 8)
+    int accum_width = 4;     // elements per accumulate work item: 4 or 8
+    int nontemporal = 1;     // 1: streaming loads/stores carry the non-temporal hint
+    int max_grid_x = 0;      // 0: one block per tile; > 0: cap and loop (persistent style)
+};
+Tuning &tuning();
+
+// Kernel launchers (odc_kernels.hip).  All return a hipError_t as int.  `ptrs` holds the
+// device base pointers of ranks [r0, r0 + nr), nr <= kRanksPerLaunch.
+int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int64_t S, int64_t N,
+                       void *stream);
+int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64_t S, int64_t N,
+                      bool atomic, void *stream);
+int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, void *stream);
+int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr,
+                          void *full, void *stream);
+int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr,
+                         const void *grad, bool atomic, void *stream);
+int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream);
+int launch_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
+}  // namespace odc
+
+// The opaque handle of the C ABI.
+struct odc_layout {
+    odc::HostLayout host;
+    bool host_only = true;
+    int device = -1;
+    void *d_blob = nullptr;  // one hipMalloc holding shard_off, desc and chunk_first
+    odc::BatchTable table{};
+    std::mutex mu;
+    // ordered-mode history: accum_shards[0] -> last (worker, microbatch)
+    std::unordered_map<const void *, std::pair<int, int>> last;
+};

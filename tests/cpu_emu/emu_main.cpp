@@ -1,0 +1,205 @@
+// CPU emulation driver for the ODC kernels (test infrastructure only).
+//
+// Reads one case from a directory, runs the REAL kernel source (odc_device.h) on the host
+// one thread at a time under AddressSanitizer/UBSan, and writes the outputs back.  Every
+// rank buffer is its own exactly-sized heap block, so any access outside the valid range of
+// a buffer is reported.  The test compares the outputs with the CPU oracle.
+//
+// usage: emu <dir> <op> <R> <unroll> <nt> <width> <atomic> <grid_cap>
+//   dir holds numel.i64 [T]; arenas.u16 [R*arena] (gather); full.u16 [full] (gather in/out);
+//   grad.u16 [full] and acc.f32 [R*arena] (accum / reset, in/out)
+#include "hip_shim.h"
+
+#include <cstdio>
+#include <cstdlib>
+#include <string>
+#include <vector>
+
+#include "../../include/odc.h"
+#include "../../paper_2601_19362_amd/csrc/odc_device.h"
+
+namespace {
+
+template <typename T>
+std::vector<T> read_file(const std::string &path)
+{
+    FILE *f = std::fopen(path.c_str(), "rb");
+    if (!f) {
+        std::fprintf(stderr, "cannot open %s\n", path.c_str());
+        std::exit(2);
+    }
+    std::fseek(f, 0, SEEK_END);
+    long n = std::ftell(f);
+    std::fseek(f, 0, SEEK_SET);
+    std::vector<T> v(static_cast<size_t>(n) / sizeof(T));
+    if (n && std::fread(v.data(), 1, static_cast<size_t>(n), f) != static_cast<size_t>(n)) std::exit(2);
+    std::fclose(f);
+    return v;
+}
+
+template <typename T>
+void write_file(const std::string &path, const T *p, size_t n)
+{
+    FILE *f = std::fopen(path.c_str(), "wb");
+    if (!f || (n && std::fwrite(p, sizeof(T), n, f) != n)) std::exit(2);
+    std::fclose(f);
+}
+
+template <typename F>
+void run_grid(unsigned gx, unsigned gy, F &&kernel)
+{
+    gridDim.x = gx;
+    gridDim.y = gy;
+    blockDim.x = 256;
+    for (unsigned y = 0; y < gy; ++y)
+        for (unsigned x = 0; x < gx; ++x)
+            for (unsigned t = 0; t < 256; ++t) {
+                blockIdx.x = x;
+                blockIdx.y = y;
+                threadIdx.x = t;
+                kernel();
+            }
+}
+
+#define EMU_DISPATCH(UN, NTF, CALL)                                                       \
+    do {                                                                                  \
+        if (NTF) {                                                                        \
+            switch (UN) {                                                                 \
+                case 1: { constexpr int U_ = 1; constexpr bool NT_ = true; CALL; } break;  \
+                case 2: { constexpr int U_ = 2; constexpr bool NT_ = true; CALL; } break;  \
+                case 8: { constexpr int U_ = 8; constexpr bool NT_ = true; CALL; } break;  \
+                default: { constexpr int U_ = 4; constexpr bool NT_ = true; CALL; } break; \
+            }                                                                             \
+        } else {                                                                          \
+            switch (UN) {                                                                 \
+                case 1: { constexpr int U_ = 1; constexpr bool NT_ = false; CALL; } break;  \
+                case 2: { constexpr int U_ = 2; constexpr bool NT_ = false; CALL; } break;  \
+                case 8: { constexpr int U_ = 8; constexpr bool NT_ = false; CALL; } break;  \
+                default: { constexpr int U_ = 4; constexpr bool NT_ = false; CALL; } break; \
+            }                                                                             \
+        }                                                                                 \
+    } while (0)
+
+}  // namespace
+
+int main(int argc, char **argv)
+{
+    if (argc != 9) {
+        std::fprintf(stderr, "usage: emu dir op R unroll nt width atomic grid_cap\n");
+        return 2;
+    }
+    const std::string dir = argv[1], op = argv[2];
+    const int R = std::atoi(argv[3]), unroll = std::atoi(argv[4]), nt = std::atoi(argv[5]);
+    const int width = std::atoi(argv[6]), atomic = std::atoi(argv[7]), cap = std::atoi(argv[8]);
+    using namespace odc;
+
+    std::vector<int64_t> numel = read_file<int64_t>(dir + "/numel.i64");
+    HostLayout H;
+    int rc = build_host_layout(R, static_cast<int>(numel.size()), numel.data(), &H);
+    if (rc != ODC_OK) {
+        std::fprintf(stderr, "layout failed: %d\n", rc);
+        return 3;
+    }
+    const size_t arena = static_cast<size_t>(H.arena_elems), full_n = static_cast<size_t>(H.full_elems);
+    std::vector<int64_t> offs(static_cast<size_t>(H.T));
+    for (int t = 0; t < H.T; ++t) offs[static_cast<size_t>(t)] = H.desc[static_cast<size_t>(t)].shard_off;
+    BatchTable tb{offs.data(), H.desc.data(), H.chunk_first.data(), H.arena_elems, H.T};
+    const bool flat = H.T == 1;
+    const int64_t S = H.desc[0].S, N = H.desc[0].numel;
+
+    if (op == "gather") {
+        std::vector<uint16_t> all = read_file<uint16_t>(dir + "/arenas.u16");
+        std::vector<uint16_t> full_in = read_file<uint16_t>(dir + "/full.u16");
+        if (all.size() != arena * static_cast<size_t>(R) || full_in.size() != full_n) return 4;
+        // exactly-sized heap blocks (malloc returns 16-byte alignment, like device memory),
+        // so the sanitizer sees any access past the last element
+        std::vector<uint16_t *> bufs(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            bufs[r] = static_cast<uint16_t *>(std::malloc(arena * 2));
+            std::memcpy(bufs[r], all.data() + arena * r, arena * 2);
+        }
+        uint16_t *full = static_cast<uint16_t *>(std::malloc(full_n * 2));
+        std::memcpy(full, full_in.data(), full_n * 2);
+        for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+            const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+            RankPtrs rp{};
+            for (int k = 0; k < nr; ++k) rp.p[k] = bufs[r0 + k];
+            if (flat) {
+                EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 3) + 1, 256 * U_, cap), nr, [&] {
+                                 k_gather_flat<U_, NT_>(rp, full, S, N, r0);
+                             }));
+            } else {
+                EMU_DISPATCH(unroll, nt,
+                             run_grid(grid_x_for((tb.arena_elems + 7) >> 3, 256 * U_, cap), nr,
+                                      [&] { k_gather_batched<U_, NT_>(tb, rp, full, r0); }));
+            }
+        }
+        write_file(dir + "/full.out", full, full_n);
+        for (auto *b : bufs) std::free(b);
+        std::free(full);
+        return 0;
+    }
+
+    if (op == "accum" || op == "reset") {
+        std::vector<float> all = read_file<float>(dir + "/acc.f32");
+        if (all.size() != arena * static_cast<size_t>(R)) return 4;
+        std::vector<uint16_t> grad_in;
+        uint16_t *grad = nullptr;
+        if (op == "accum") {
+            grad_in = read_file<uint16_t>(dir + "/grad.u16");
+            if (grad_in.size() != full_n) return 4;
+            grad = static_cast<uint16_t *>(std::malloc(full_n * 2));
+            std::memcpy(grad, grad_in.data(), full_n * 2);
+        }
+        std::vector<float *> bufs(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            bufs[r] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(bufs[r], all.data() + arena * r, arena * 4);
+        }
+        for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+            const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+            RankPtrs rp{};
+            for (int k = 0; k < nr; ++k) rp.p[k] = bufs[r0 + k];
+            if (op == "reset") {
+                if (flat) {
+                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr,
+                                                      [&] { k_reset_flat<U_, NT_>(rp, S, N, r0); }));
+                } else {
+                    EMU_DISPATCH(unroll, nt,
+                                 run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
+                                          [&] { k_reset_batched<U_, NT_>(tb, rp, r0); }));
+                }
+            } else if (flat) {
+                if (atomic) {
+                    EMU_DISPATCH(unroll, 0, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr, [&] {
+                                     k_accum_flat<U_, 4, NT_, true>(rp, grad, S, N, r0);
+                                 }));
+                } else if (width == 8) {
+                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 3) + 1, 256 * U_, cap), nr, [&] {
+                                     k_accum_flat<U_, 8, NT_, false>(rp, grad, S, N, r0);
+                                 }));
+                } else {
+                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr, [&] {
+                                     k_accum_flat<U_, 4, NT_, false>(rp, grad, S, N, r0);
+                                 }));
+                }
+            } else if (atomic) {
+                EMU_DISPATCH(unroll, 0,
+                             run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
+                                      [&] { k_accum_batched<U_, NT_, true>(tb, rp, grad, r0); }));
+            } else {
+                EMU_DISPATCH(unroll, nt,
+                             run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
+                                      [&] { k_accum_batched<U_, NT_, false>(tb, rp, grad, r0); }));
+            }
+        }
+        std::vector<float> out(arena * static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) std::memcpy(out.data() + arena * r, bufs[r], arena * 4);
+        write_file(dir + "/acc.out", out.data(), out.size());
+        for (auto *b : bufs) std::free(b);
+        std::free(grad);
+        return 0;
+    }
+    std::fprintf(stderr, "unknown op %s\n", op.c_str());
+    return 2;
+}

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Gather and ordered scatter-accumulate must be bit-exact;
+reset must give +0.0f; nothing outside the valid elements may change."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_19362_amd import binding as odc
+from paper_2601_19362_amd import inputs
+
+from gpu_util import (FULL16, PAD16, PAD32, DeviceCase, assert_bits_equal, host_arenas_from_flats,
+                      to_dev_u16, to_host_u16)
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(oracle, numel, R, contribs, seed, grad_sigma=1e-3, prange=(-0.05, 0.05)):
+    """Gather once, reset, then apply `contribs` = [(worker, microbatch)] in order; compare all
+    buffers (including padding, gaps and guards) with the oracle."""
+    print(f"case R={R} T={len(numel)} total={sum(numel)} C={len(contribs)} seed={seed}", flush=True)
+    case = DeviceCase(R, numel)
+    flats = [inputs.uniform_bf16(n, prange[0], prange[1], seed=(seed, 1, t)) for t, n in enumerate(numel)]
+    arenas = host_arenas_from_flats(oracle, flats, R, case.S, case.shard_off, case.arena)
+    case.load_params(arenas)
+
+    # gather
+    case.layout.gather(case.param_ptrs, case.full.t)
+    got_full = to_host_u16(case.full.t)
+    want_full = np.full(case.full_n, FULL16, dtype=np.uint16)
+    oracle.gather_batched(arenas, numel, case.shard_off, case.full_off, want_full)
+    assert_bits_equal(got_full, want_full, "gather")
+    for t, n in enumerate(numel):  # round trip: the flat parameter comes back bit for bit
+        assert np.array_equal(got_full[case.full_off[t]:case.full_off[t] + n], flats[t])
+    for p, a in zip(case.params, arenas):  # sources untouched
+        assert np.array_equal(to_host_u16(p.t), a)
+
+    # reset + ordered accumulate
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    oracle.reset_batched(acc_host, numel, case.shard_off)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"reset rank {r}")
+    for (w, m) in contribs:
+        g = inputs.normal_bf16(case.full_n, grad_sigma, seed=(seed, 2, w, m))
+        case.grad.t.copy_(to_dev_u16(g))
+        case.layout.scatter_accumulate(case.grad.t, case.acc_ptrs, w, m)
+        oracle.accumulate_batched(g, acc_host, numel, case.shard_off, case.full_off)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"accumulate rank {r}")
+    torch.cuda.synchronize()
+    case.check_guards()
+    case.close()
+
+
+def contributions(M):
+    return [(w, m) for w in range(len(M)) for m in range(M[w])]
+
+
+def test_tiny_config(oracle):
+    """Config 1: R = 4, N = 1,048,589 (tail padding, 8-byte-misaligned shard boundaries)."""
+    w = inputs.workload("tiny")
+    run_case(oracle, list(w.numel), w.R, contributions(inputs.microbatch_counts(w)), seed=w.seed)
+
+
+@pytest.mark.parametrize("N,R", [(1, 1), (1, 64), (7, 3), (64, 64), (65, 64), (1000, 7), (4099, 8),
+                                 (8 * 1024 * 3 + 5, 4), (524_309, 2), (1_000_003, 33),
+                                 (4 * 1024 * 1024, 8), (3_000_001, 16), (350, 70)])
+def test_single_tensor_shapes(oracle, N, R):
+    M = [1 + (w % 3 == 0) for w in range(R)]
+    run_case(oracle, [N], R, contributions(M)[:6], seed=N % 1000 + R)
+
+
+@pytest.mark.parametrize("numel,R", [
+    ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+    ([3, 1, 1, 2, 70, 5000, 2, 2, 129, 1], 64),
+    ([30000, 17, 2048, 2049, 1_000_001], 5),
+    ([5] * 70 + [100_000], 70),
+])
+def test_batched_shapes(oracle, numel, R):
+    run_case(oracle, numel, R, [(0, 0), (0, 1), (R - 1, 0)], seed=len(numel) + R, grad_sigma=1e-2,
+             prange=(-1, 1))
+
+
+def test_stress_config(oracle):
+    """Config 5: 10,000 flat params, R = 64, one batched launch per call."""
+    w = inputs.workload("stress")
+    M = inputs.microbatch_counts(w)
+    run_case(oracle, list(w.numel), w.R, contributions(M)[:5], seed=w.seed, grad_sigma=w.grad_sigma,
+             prange=w.param_range)
+
+
+@pytest.mark.parametrize("knobs", [
+    dict(gather_unroll=1, accum_unroll=1, nontemporal=0, accum_width=4, max_grid_x=0),
+    dict(gather_unroll=2, accum_unroll=2, nontemporal=1, accum_width=8, max_grid_x=0),
+    dict(gather_unroll=8, accum_unroll=8, nontemporal=1, accum_width=4, max_grid_x=7),
+    dict(gather_unroll=4, accum_unroll=8, nontemporal=0, accum_width=8, max_grid_x=512),
+])
+def test_results_do_not_depend_on_launch_knobs(oracle, knobs):
+    try:
+        for k, v in knobs.items():
+            odc.tune(k, v)
+        run_case(oracle, [2_000_003], 4, [(0, 0), (1, 0), (1, 1)], seed=77)
+        run_case(oracle, [30000, 17, 2048, 2049, 100_001], 5, [(0, 0), (4, 2)], seed=78)
+    finally:
+        for k, v in dict(gather_unroll=4, accum_unroll=4, nontemporal=1, accum_width=4, max_grid_x=0).items():
+            odc.tune(k, v)
+
+
+def test_special_values(oracle):
+    """Subnormals are kept, signed zeros and infinities follow IEEE-754, NaN stays NaN."""
+    specials = np.array([0x0001, 0x0003, 0x8001, 0x007F, 0x0080, 0x8000, 0x0000, 0x7F80, 0xFF80,
+                         0x7FC0, 0x3F80, 0xBF80, 0x7F7F, 0xFF7F], dtype=np.uint16)
+    N, R = 4096 + 11, 4
+    rng = np.random.default_rng(3)
+    gs = [specials[rng.integers(0, specials.size, size=N)] for _ in range(4)]
+    case = DeviceCase(R, [N], with_params=False)
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    oracle.reset(acc_host, N)
+    for k, g in enumerate(gs):
+        case.grad.t.copy_(to_dev_u16(g))
+        case.layout.scatter_accumulate(case.grad.t, case.acc_ptrs, 0, k)
+        oracle.accumulate(g, acc_host, N)
+    saw_sub = saw_nan = False
+    for r, a in enumerate(case.acc_host()):
+        want = acc_host[r]
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(a), nan)            # NaN-ness; payloads are not pinned
+        assert_bits_equal(a[~nan], want[~nan], f"specials rank {r}")
+        valid = want != PAD32
+        saw_sub |= bool(((np.abs(want[valid & ~nan]) < 1.17549435e-38) & (want[valid & ~nan] != 0)).any())
+        saw_nan |= bool(nan.any())
+    assert saw_sub and saw_nan
+    case.check_guards()
+    case.close()
+
+
+def test_ordered_mode_history_and_reset(oracle):
+    case = DeviceCase(4, [1000], with_params=False)
+    L = case.layout
+    L.reset_accum(case.acc_ptrs)
+    g = to_dev_u16(inputs.normal_bf16(1000, 1e-3, seed=5))
+    case.grad.t.copy_(g)
+    sa = lambda w, m, flags=odc.ODC_ORDERED: odc.scatter_accumulate_rc(L, case.grad.t, case.acc_ptrs, w, m, flags)
+    assert sa(0, 0) == 0
+    assert sa(0, 0) == odc.ODC_ERR_ORDER          # same slot twice
+    assert sa(0, 2) == 0                           # gaps are fine
+    assert sa(0, 1) == odc.ODC_ERR_ORDER          # microbatch going back
+    assert sa(2, 0) == 0
+    assert sa(1, 5) == odc.ODC_ERR_ORDER          # worker going back
+    assert sa(1, 5, odc.ODC_UNORDERED) == 0        # unordered calls are not checked
+    before = [a.copy() for a in case.acc_host()]
+    assert sa(1, 0) == odc.ODC_ERR_ORDER
+    for a, b in zip(case.acc_host(), before):      # a refused call enqueues nothing
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # a second accumulator set has its own history
+    other = [torch.zeros(case.arena, dtype=torch.float32, device="cuda") for _ in range(4)]
+    assert odc.scatter_accumulate_rc(L, case.grad.t, other, 0, 0) == 0
+    L.reset_accum(case.acc_ptrs)
+    assert sa(0, 0) == 0                           # reset forgets the history
+    torch.cuda.synchronize()
+    case.close()
+
+
+def test_unordered_mode_within_tolerance(oracle):
+    """Unordered mode: |x - ref64| <= 1e-6 * sum|g| per element against a float64 sum, with
+    contributions issued in a scrambled order from two streams."""
+    N, R = 1_000_003, 8
+    M = [2, 1, 3, 1, 2, 2, 1, 2]
+    grads = [[inputs.normal_bf16(N, 1e-3, seed=(91, w, m)) for m in range(M[w])] for w in range(R)]
+    case = DeviceCase(R, [N], with_params=False)
+    case.layout.reset_accum(case.acc_ptrs)
+    torch.cuda.synchronize()
+    order = contributions(M)
+    rng = np.random.default_rng(1)
+    rng.shuffle(order)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dev = {(w, m): to_dev_u16(grads[w][m]) for (w, m) in order}
+    torch.cuda.synchronize()
+    for k, (w, m) in enumerate(order):
+        case.layout.scatter_accumulate(dev[(w, m)], case.acc_ptrs, w, m, odc.ODC_UNORDERED,
+                                       stream=streams[k % 2])
+    torch.cuda.synchronize()
+    sum64, abs64 = oracle.fp64_sum_shards(grads, N, R)
+    worst = 0.0
+    for r, a in enumerate(case.acc_host()):
+        valid = max(0, min(case.S[0], N - r * case.S[0]))
+        err = np.abs(a[:valid].astype(np.float64) - sum64[r][:valid])
+        bound = 1e-6 * abs64[r][:valid]
+        assert (err <= bound).all()
+        worst = max(worst, float((err / np.maximum(abs64[r][:valid], 1e-300)).max()))
+        assert (a[valid:] == PAD32).all()
+    print(f"unordered worst |err|/sum|g| = {worst:.3e}", flush=True)
+    case.check_guards()
+    case.close()
+
+
+def test_non_default_stream_and_probe_copy():
+    s = torch.cuda.Stream()
+    n = 1 << 20
+    src = torch.arange(n, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    torch.cuda.synchronize()
+    odc.probe_copy(dst, src, n * 4, stream=s)
+    s.synchronize()
+    assert torch.equal(src, dst)

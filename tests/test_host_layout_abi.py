@@ -1,0 +1,154 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads and exports every
+symbol the header declares, the layout arithmetic agrees with the closed forms and with the
+oracle, and argument errors are reported before anything is launched."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2601_19362_amd import binding as odc
+from paper_2601_19362_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "odc.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(odc_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(odc.EXPORTS)
+    lib = odc.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_error_strings_and_codes():
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
+        assert odc.strerror(code) and "unknown" not in odc.strerror(code)
+    assert "unknown" in odc.strerror(-99)
+    header = open(os.path.join(ROOT, "include", "odc.h")).read()
+    for name in ("ODC_ERR_INVALID_ARG", "ODC_ERR_ALIGNMENT", "ODC_ERR_ORDER", "ODC_ERR_OVERFLOW",
+                 "ODC_ERR_HIP", "ODC_ERR_NO_DEVICE", "ODC_ERR_NOMEM", "ODC_MAX_RANKS",
+                 "ODC_LAYOUT_HOST_ONLY", "ODC_ORDERED", "ODC_UNORDERED"):
+        m = re.search(rf"#define {name} \(?(-?\d+)\)?", header)
+        assert m and int(m.group(1)) == getattr(odc, name), name
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 8, 16, 33, 64, 100])
+def test_single_tensor_layout_matches_closed_form_and_oracle(oracle, R):
+    for N in [1, 2, 7, 63, 64, 65, 1000, 4099, 1_048_589, 46_795_776, 487_598_080]:
+        L = odc.Layout(R, [N], host_only=True)
+        S = -(-N // R)
+        assert L.num_ranks() == R and L.num_tensors() == 1 and L.numel(0) == N
+        assert L.shard_elems(0) == S == oracle.shard_elems(N, R)
+        assert L.rank_arena_elems() == S and L.full_elems() == N
+        assert L.shard_offset(0) == 0 and L.full_offset(0) == 0
+        valid = [L.valid_elems(0, r) for r in range(R)]
+        assert valid == [oracle.valid_elems(N, R, r) for r in range(R)]
+        assert sum(valid) == N
+        L.close()
+
+
+def test_multi_tensor_placement():
+    """Tensor starts are multiples of 8 elements, in order, without overlap; the last tensor
+    is not padded."""
+    w = inputs.workload("stress")
+    L = odc.Layout(w.R, w.numel, host_only=True)
+    so = np.array([L.shard_offset(t) for t in range(w.T)])
+    fo = np.array([L.full_offset(t) for t in range(w.T)])
+    n = np.array(w.numel)
+    S = -(-n // w.R)
+    assert (so % 8 == 0).all() and (fo % 8 == 0).all()
+    assert so[0] == 0 and fo[0] == 0
+    assert np.array_equal(so[1:], np.cumsum((S + 7) // 8 * 8)[:-1])
+    assert np.array_equal(fo[1:], np.cumsum((n + 7) // 8 * 8)[:-1])
+    assert L.rank_arena_elems() == so[-1] + S[-1]
+    assert L.full_elems() == fo[-1] + n[-1]
+    assert [L.shard_elems(t) for t in range(0, w.T, 997)] == S[::997].tolist()
+    L.close()
+
+
+def test_query_range_errors():
+    L = odc.Layout(4, [10, 20], host_only=True)
+    assert L.numel(2) == -1 and L.numel(-1) == -1 and L.shard_elems(5) == -1
+    assert L.valid_elems(0, 4) == -1 and L.valid_elems(0, -1) == -1 and L.valid_elems(2, 0) == -1
+    assert L.shard_offset(2) == -1 and L.full_offset(-1) == -1
+    lib = odc.lib()
+    assert lib.odc_num_ranks(None) == -1 and lib.odc_full_elems(None) == -1
+    lib.odc_free_layout(None)  # ignored
+
+
+def test_init_argument_errors():
+    def code(R, numel, flags=odc.ODC_LAYOUT_HOST_ONLY, T=None):
+        import ctypes
+        arr = (ctypes.c_int64 * max(len(numel), 1))(*numel)
+        h = ctypes.c_void_p()
+        rc = odc.lib().odc_init_layout(R, len(numel) if T is None else T, arr, flags, ctypes.byref(h))
+        if rc == 0:
+            odc.lib().odc_free_layout(h)
+        else:
+            assert not h.value
+        return rc
+
+    assert code(4, [10]) == 0
+    assert code(0, [10]) == odc.ODC_ERR_INVALID_ARG
+    assert code(-3, [10]) == odc.ODC_ERR_INVALID_ARG
+    assert code(odc.ODC_MAX_RANKS + 1, [10]) == odc.ODC_ERR_INVALID_ARG
+    assert code(odc.ODC_MAX_RANKS, [10]) == 0
+    assert code(4, [], T=0) == odc.ODC_ERR_INVALID_ARG
+    assert code(4, [10, 0]) == odc.ODC_ERR_INVALID_ARG
+    assert code(4, [-5]) == odc.ODC_ERR_INVALID_ARG
+    assert code(4, [10], flags=2) == odc.ODC_ERR_INVALID_ARG
+    assert code(4, [2 ** 62]) == odc.ODC_ERR_OVERFLOW
+    assert code(4, [2 ** 58, 2 ** 58, 2 ** 58]) == odc.ODC_ERR_OVERFLOW
+    import ctypes
+    assert odc.lib().odc_init_layout(4, 1, None, 1, ctypes.byref(ctypes.c_void_p())) == odc.ODC_ERR_INVALID_ARG
+    arr = (ctypes.c_int64 * 1)(5)
+    assert odc.lib().odc_init_layout(4, 1, arr, 1, None) == odc.ODC_ERR_INVALID_ARG
+
+
+def test_launch_argument_errors_are_found_before_any_launch():
+    """With a host-only layout nothing can be launched, so every code below comes from the
+    host-side validation (fake, never dereferenced addresses stand in for device pointers)."""
+    L = odc.Layout(4, [1000], host_only=True)
+    good = [0x1000, 0x2000, 0x3000, 0x4000]
+    assert odc.gather_rc(L, good, 0x8000, 0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.gather_rc(L, good, None, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.gather_rc(L, None, 0x8000, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.gather_rc(L, [0x1000, None, 0x3000, 0x4000], 0x8000, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.gather_rc(L, [0x1000, 0x2008, 0x3000, 0x4000], 0x8000, 0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.gather_rc(L, good, 0x8002, 0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.lib().odc_gather(None, None, None, None) == odc.ODC_ERR_INVALID_ARG
+
+    sa = odc.scatter_accumulate_rc
+    assert sa(L, 0x8000, good, 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_NO_DEVICE
+    assert sa(L, 0x8000, good, 3, 7, odc.ODC_UNORDERED, 0) == odc.ODC_ERR_NO_DEVICE
+    assert sa(L, None, good, 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_INVALID_ARG
+    assert sa(L, 0x8000, good, 4, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_INVALID_ARG
+    assert sa(L, 0x8000, good, -1, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_INVALID_ARG
+    assert sa(L, 0x8000, good, 0, -1, odc.ODC_ORDERED, 0) == odc.ODC_ERR_INVALID_ARG
+    assert sa(L, 0x8000, good, 0, 0, 5, 0) == odc.ODC_ERR_INVALID_ARG
+    assert sa(L, 0x8004, good, 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_ALIGNMENT
+    assert sa(L, 0x8000, [0x1000, 0x2000, 0x3004, 0x4000], 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_ALIGNMENT
+
+    assert odc.reset_accum_rc(L, good, 0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.reset_accum_rc(L, None, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.reset_accum_rc(L, [0x1000, 0x2000, 0x3000, 0x4001], 0) == odc.ODC_ERR_ALIGNMENT
+    L.close()
+
+
+def test_probe_and_tune_argument_errors():
+    lib = odc.lib()
+    assert lib.odc_probe_copy(None, 0x1000, 16, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_probe_copy(0x1000, 0x2000, 24, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_probe_copy(0x1000, 0x2000, -16, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_probe_copy(0x1004, 0x2000, 16, None) == odc.ODC_ERR_ALIGNMENT
+    assert lib.odc_tune(b"gather_unroll", 3) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(b"no_such_knob", 1) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(None, 1) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(b"gather_unroll", 4) == 0
+    assert lib.odc_tune(b"accum_unroll", 4) == 0
+    assert lib.odc_tune(b"accum_width", 4) == 0
+    assert lib.odc_tune(b"nontemporal", 1) == 0
+    assert lib.odc_tune(b"max_grid_x", 0) == 0

@@ -1,0 +1,113 @@
+"""The kernel source run on the CPU, one thread at a time, under AddressSanitizer and UBSan.
+
+tests/cpu_emu/emu_main.cpp compiles paper_2601_19362_amd/csrc/odc_device.h (the real kernels)
+against a small host shim.  Every rank buffer is an exactly-sized heap block, so an index
+error in a kernel shows up here, on the CPU, as a sanitizer report instead of a GPU fault.
+The outputs are compared with the CPU oracle bit for bit.  This checks the kernels' indexing
+and arithmetic logic, not the GPU build: parity of the HIP path proper is tests/test_gpu_*.py.
+"""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2601_19362_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CLANG = "/opt/rocm/lib/llvm/bin/clang++"
+PAD16 = 0xDEAD
+PAD32 = np.float32(-12345.678)
+
+pytestmark = pytest.mark.skipif(not os.path.exists(CLANG), reason="ROCm clang++ not present")
+
+
+@pytest.fixture(scope="module")
+def emu(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("emu") / "emu")
+    subprocess.run([CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=all", "-ffp-contract=off",
+                    os.path.join(ROOT, "tests", "cpu_emu", "emu_main.cpp"),
+                    os.path.join(ROOT, "paper_2601_19362_amd", "csrc", "odc_layout.cpp"),
+                    "-o", exe], check=True)
+    return exe
+
+
+def placement(numel, R):
+    """Tensor starts at multiples of 8 elements (the library's documented placement rule)."""
+    S = [-(-n // R) for n in numel]
+    so, fo, a, f = [], [], 0, 0
+    for n, s in zip(numel, S):
+        so.append(a)
+        fo.append(f)
+        a += (s + 7) // 8 * 8
+        f += (n + 7) // 8 * 8
+    return S, so, fo, so[-1] + S[-1], fo[-1] + numel[-1]
+
+
+def run(emu, d, op, R, unroll=4, nt=1, width=4, atomic=0, cap=0):
+    p = subprocess.run([emu, str(d), op, str(R), str(unroll), str(nt), str(width), str(atomic),
+                        str(cap)], capture_output=True, text=True,
+                       env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0"})
+    assert p.returncode == 0, p.stderr[-3000:]
+
+
+def make_case(oracle, numel, R, seed):
+    S, so, fo, arena, full_n = placement(numel, R)
+    arenas = [np.full(arena, PAD16, dtype=np.uint16) for _ in range(R)]
+    flats = []
+    for t, n in enumerate(numel):
+        flat = inputs.uniform_bf16(n, -1, 1, seed=(seed, t))
+        flats.append(flat)
+        for r, sh in enumerate(oracle.make_shards(flat, R, pad_bits=PAD16)):
+            arenas[r][so[t]:so[t] + S[t]] = sh
+    return S, so, fo, arena, full_n, arenas, flats
+
+
+CASES = [
+    ([1], 1), ([1], 64), ([7], 3), ([64], 64), ([65], 64), ([1000], 7), ([4099], 8),
+    ([8 * 1024 * 3 + 5], 4),          # several full tiles + ragged tail, misaligned boundaries
+    ([262_148 * 2 + 13], 2),
+    ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+    ([3, 1, 1, 2, 70, 5000, 2, 2, 129, 1], 64),
+    ([30000, 17, 2048, 2049], 5),
+    ([5] * 70, 70),                   # more than 64 ranks: two launch groups
+]
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("unroll,nt,cap", [(4, 1, 0), (1, 0, 3), (8, 1, 1)])
+def test_emulated_gather(oracle, emu, tmp_path, numel, R, unroll, nt, cap):
+    S, so, fo, arena, full_n, arenas, flats = make_case(oracle, numel, R, seed=1)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    np.concatenate(arenas).tofile(tmp_path / "arenas.u16")
+    np.full(full_n, 0xBEEF, dtype=np.uint16).tofile(tmp_path / "full.u16")
+    run(emu, tmp_path, "gather", R, unroll=unroll, nt=nt, cap=cap)
+    got = np.fromfile(tmp_path / "full.out", dtype=np.uint16)
+    want = np.full(full_n, 0xBEEF, dtype=np.uint16)
+    oracle.gather_batched(arenas, numel, so, fo, want)
+    assert np.array_equal(got, want)
+    for t, n in enumerate(numel):
+        assert np.array_equal(got[fo[t]:fo[t] + n], flats[t])
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("unroll,nt,width,atomic,cap", [(4, 1, 4, 0, 0), (2, 0, 8, 0, 2), (8, 1, 4, 1, 0),
+                                                        (1, 1, 8, 0, 0)])
+def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, unroll, nt, width, atomic, cap):
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    run(emu, tmp_path, "reset", R, unroll=unroll, nt=nt, cap=cap)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    oracle.reset_batched(acc, numel, so)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+    for k in range(3):
+        g = inputs.normal_bf16(full_n, 1e-2, seed=(2, k))
+        g.tofile(tmp_path / "grad.u16")
+        got.tofile(tmp_path / "acc.f32")
+        run(emu, tmp_path, "accum", R, unroll=unroll, nt=nt, width=width, atomic=atomic, cap=cap)
+        got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+        oracle.accumulate_batched(g, acc, numel, so, fo)
+        assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
