@@ -38,8 +38,25 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU-baseline sample time")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE")
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="measured HBM bytes per accumulate launch (from rocprofv3 --pmc runs)")
+                    help="measured HBM bytes per accumulate launch (from rocprofv3 --pmc runs); "
+                         "default: the figure recorded in profiles/ for the 7b workload")
     return ap.parse_args()
+
+
+def recorded_traffic(workload, tune):
+    """HBM bytes per accumulate launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a plain copy of known size) and written down in profiles/; None if the run is
+    not the configuration that summary covers."""
+    if workload != "7b" or tune:
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "odc_kernels_7b_workload.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def build_state(w, layers, torch, odc, inputs):
@@ -176,7 +193,7 @@ def cpu_baseline(w, target_s):
     ops["gather"]()
     nbytes = total * (4 + 2 * 4)
     n_acc = 0
-    while n_acc < 2 or (time.perf_counter() - t0 < target_s and n_acc < 256):
+    while n_acc < 2 or (time.perf_counter() - t0 < target_s and n_acc < 4096):
         ops["accum"]()
         n_acc += 1
         nbytes += total * 10
@@ -262,7 +279,8 @@ def main():
             "bound": "hbm", "kernel": "scatter_accumulate (ordered)",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": args.traffic_bytes,
+            "traffic": (args.traffic_bytes if args.traffic_bytes is not None
+                        else recorded_traffic(args.workload, args.tune)),
             "avg_launch_ms": round(acc_ms, 4), "launches_timed": (len(events.pairs) if events else 0),
             "algorithmic_bytes_per_launch": 10 * total,
         },

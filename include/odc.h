@@ -146,9 +146,16 @@ int odc_last_hip_error(void);
  * odc_probe_copy: plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both
  * pointers 16-byte aligned) on `stream`: a kernel of known traffic used to calibrate
  * hardware counters and to measure this GPU's copy ceiling next to the ODC kernels.
- * odc_tune: set a launch knob by name for all later calls of this process ("gather_unroll",
- * "accum_unroll", "nontemporal", "max_grid_x", "accum_width"); returns ODC_ERR_INVALID_ARG
- * for an unknown name or a value out of range.  Results never depend on the knobs.
+ * odc_tune: set a launch knob by name for all later calls of this process:
+ *   "gather_threads" / "accum_threads" / "reset_threads"  workgroup size of the single-tensor
+ *                                                          kernels: 64, 128 or 256
+ *   "gather_unroll" / "accum_unroll" / "reset_unroll"     16-byte work items per thread: 1, 2, 4
+ *   "nontemporal"   0 or 1: streaming accesses carry the non-temporal hint
+ *   "tile_remap"    0 or 1: each XCD sweeps its own contiguous eighth of the tiles
+ *   "max_grid_x"    0 = one workgroup per tile; > 0 caps the grid, workgroups then loop
+ *   "defaults"      with value 0: every knob back to its built-in default
+ * Returns ODC_ERR_INVALID_ARG for an unknown name or a value out of range.  Results never
+ * depend on the knobs.
  */
 int odc_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
 int odc_tune(const char *knob, int value);

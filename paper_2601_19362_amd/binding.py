@@ -243,3 +243,7 @@ def tune(knob: str, value: int) -> None:
     rc = lib().odc_tune(knob.encode(), int(value))
     if rc != ODC_OK:
         raise OdcError(rc, f"odc_tune({knob}={value})")
+
+
+def reset_tuning() -> None:
+    tune("defaults", 0)

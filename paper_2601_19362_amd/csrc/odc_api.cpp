@@ -270,11 +270,18 @@ int odc_tune(const char *knob, int value)
 {
     if (!knob) return ODC_ERR_INVALID_ARG;
     odc::Tuning &t = odc::tuning();
-    const bool unroll_ok = value == 1 || value == 2 || value == 4 || value == 8;
-    if (!std::strcmp(knob, "gather_unroll") && unroll_ok) t.gather_unroll = value;
+    const bool unroll_ok = value == 1 || value == 2 || value == 4;
+    const bool threads_ok = value == 64 || value == 128 || value == 256;
+    const bool flag_ok = value == 0 || value == 1;
+    if (!std::strcmp(knob, "defaults") && value == 0) t = odc::Tuning{};
+    else if (!std::strcmp(knob, "gather_unroll") && unroll_ok) t.gather_unroll = value;
     else if (!std::strcmp(knob, "accum_unroll") && unroll_ok) t.accum_unroll = value;
-    else if (!std::strcmp(knob, "accum_width") && (value == 4 || value == 8)) t.accum_width = value;
-    else if (!std::strcmp(knob, "nontemporal") && (value == 0 || value == 1)) t.nontemporal = value;
+    else if (!std::strcmp(knob, "reset_unroll") && unroll_ok) t.reset_unroll = value;
+    else if (!std::strcmp(knob, "gather_threads") && threads_ok) t.gather_threads = value;
+    else if (!std::strcmp(knob, "accum_threads") && threads_ok) t.accum_threads = value;
+    else if (!std::strcmp(knob, "reset_threads") && threads_ok) t.reset_threads = value;
+    else if (!std::strcmp(knob, "nontemporal") && flag_ok) t.nontemporal = value;
+    else if (!std::strcmp(knob, "tile_remap") && flag_ok) t.tile_remap = value;
     else if (!std::strcmp(knob, "max_grid_x") && value >= 0) t.max_grid_x = value;
     else return ODC_ERR_INVALID_ARG;
     return ODC_OK;

@@ -26,8 +26,6 @@
 namespace odc {
 namespace {
 
-constexpr int kThreads = 256;
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -91,31 +89,48 @@ __device__ __forceinline__ void add_one(float *a, float v)
 }
 
 // ------------------------------------------------------------------------------------ flat
-// One flat parameter (T = 1).  grid = (tiles, ranks); a tile is kThreads * U work items,
-// item (u, lane) = tile_base + u * kThreads + lane, so each wave instruction touches one
+// One flat parameter (T = 1).  grid = (tiles, ranks); a tile is TPB * U work items,
+// item (u, lane) = tile_base + u * TPB + lane, so each wave instruction touches one
 // contiguous run.  Full tiles run without per-item guards: all U loads are issued back to
 // back and only then consumed, which keeps U independent requests per lane in flight.
+//
+// Tile order.  The hardware hands consecutive workgroup ids to the 8 XCDs in turn.  With
+// remap = 0 tile = workgroup id: the whole chip sweeps one compact address window.  With
+// remap = 1 the tile space is cut into 8 contiguous parts and workgroup id w takes tile
+// (w mod 8) * part + w / 8, so each XCD sweeps its own contiguous part.
 
-template <int U, bool NT, bool GUARD>
+__device__ __forceinline__ int64_t tile_of(int64_t slot, int64_t ntiles, int remap)
+{
+    if (!remap) return slot;
+    const int64_t part = (ntiles + 7) >> 3;
+    return (slot & 7) * part + (slot >> 3);
+}
+
+__device__ __forceinline__ int64_t slots_of(int64_t ntiles, int remap)
+{
+    return remap ? ((ntiles + 7) >> 3) << 3 : ntiles;
+}
+
+template <int TPB, int U, bool NT, bool GUARD>
 __device__ __forceinline__ void gather_tile(const uint16_t *__restrict__ bsrc, u32x4 *__restrict__ bdst,
                                             int64_t v0, int64_t nvec)
 {
     u32x4 reg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t v = v0 + u * kThreads;
+        const int64_t v = v0 + u * TPB;
         if (!GUARD || v < nvec) reg[u] = ld_u128_unaligned<NT>(bsrc + 8 * v);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t v = v0 + u * kThreads;
+        const int64_t v = v0 + u * TPB;
         if (!GUARD || v < nvec) st<NT>(bdst + v, reg[u]);
     }
 }
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void k_gather_flat(RankPtrs shards, uint16_t *__restrict__ full,
-                                                          int64_t S, int64_t N, int r0)
+template <int TPB, int U, bool NT>
+__global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *__restrict__ full,
+                                                     int64_t S, int64_t N, int r0, int remap)
 {
     const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
     int64_t valid = N - base;
@@ -131,11 +146,12 @@ __global__ __launch_bounds__(kThreads) void k_gather_flat(RankPtrs shards, uint1
     const uint16_t *bsrc = src + head;
     u32x4 *bdst = reinterpret_cast<u32x4 *>(dst + head);
 
-    const int64_t ntiles = (nvec + kThreads * U - 1) / (kThreads * U);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t t0 = tile * (kThreads * U);
-        if (t0 + kThreads * U <= nvec) gather_tile<U, NT, false>(bsrc, bdst, t0 + threadIdx.x, nvec);
-        else gather_tile<U, NT, true>(bsrc, bdst, t0 + threadIdx.x, nvec);
+    const int64_t ntiles = (nvec + TPB * U - 1) / (TPB * U);
+    const int64_t nslots = slots_of(ntiles, remap);
+    for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
+        const int64_t t0 = tile_of(slot, ntiles, remap) * (TPB * U);
+        if (t0 + TPB * U <= nvec) gather_tile<TPB, U, NT, false>(bsrc, bdst, t0 + threadIdx.x, nvec);
+        else if (t0 < nvec) gather_tile<TPB, U, NT, true>(bsrc, bdst, t0 + threadIdx.x, nvec);
     }
     if (blockIdx.x == 0) {
         const int t = threadIdx.x;
@@ -164,68 +180,37 @@ __device__ __forceinline__ void atomic_add4(float *a, u32x2 g)
     unsafeAtomicAdd(a + 3, widen_hi(g.y));
 }
 
-// W = 4: a work item is one accumulator vector (4 floats, 16 bytes) and 8 bytes of gradient;
-//        consecutive lanes take consecutive vectors, so every wave instruction is contiguous.
-// W = 8: a work item is 16 bytes of gradient and two adjacent accumulator vectors.
-template <int U, int W, bool NT, bool ATOMIC, bool GUARD>
+// A work item is one accumulator vector (4 floats, 16 bytes) and 8 bytes of gradient;
+// consecutive lanes take consecutive vectors, so every wave instruction is contiguous
+// (1 KiB of accumulator, 512 B of gradient).
+template <int TPB, int U, bool NT, bool ATOMIC, bool GUARD>
 __device__ __forceinline__ void accum_tile(float *__restrict__ acc, const uint16_t *__restrict__ g,
                                            int64_t q0, int64_t nitem)
 {
     f32x4 *__restrict__ accv = reinterpret_cast<f32x4 *>(acc);
-    if constexpr (W == 4) {
-        u32x2 gv[U];
-        f32x4 av[U];
+    u32x2 gv[U];
+    f32x4 av[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t q = q0 + u * kThreads;
-            if (!GUARD || q < nitem) {
-                gv[u] = ld_u64_unaligned<NT>(g + 4 * q);
-                if constexpr (!ATOMIC) av[u] = ld<NT>(accv + q);
-            }
+    for (int u = 0; u < U; ++u) {
+        const int64_t q = q0 + u * TPB;
+        if (!GUARD || q < nitem) {
+            gv[u] = ld_u64_unaligned<NT>(g + 4 * q);
+            if constexpr (!ATOMIC) av[u] = ld<NT>(accv + q);
         }
+    }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t q = q0 + u * kThreads;
-            if (!GUARD || q < nitem) {
-                if constexpr (ATOMIC) atomic_add4(acc + 4 * q, gv[u]);
-                else st<NT>(accv + q, add4(av[u], gv[u]));
-            }
-        }
-    } else {
-        u32x4 gv[U];
-        f32x4 a0[U], a1[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t q = q0 + u * kThreads;
-            if (!GUARD || q < nitem) {
-                gv[u] = ld_u128_unaligned<NT>(g + 8 * q);
-                if constexpr (!ATOMIC) {
-                    a0[u] = ld<NT>(accv + 2 * q);
-                    a1[u] = ld<NT>(accv + 2 * q + 1);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t q = q0 + u * kThreads;
-            if (!GUARD || q < nitem) {
-                const u32x2 glo = {gv[u].x, gv[u].y};
-                const u32x2 ghi = {gv[u].z, gv[u].w};
-                if constexpr (ATOMIC) {
-                    atomic_add4(acc + 8 * q, glo);
-                    atomic_add4(acc + 8 * q + 4, ghi);
-                } else {
-                    st<NT>(accv + 2 * q, add4(a0[u], glo));
-                    st<NT>(accv + 2 * q + 1, add4(a1[u], ghi));
-                }
-            }
+    for (int u = 0; u < U; ++u) {
+        const int64_t q = q0 + u * TPB;
+        if (!GUARD || q < nitem) {
+            if constexpr (ATOMIC) atomic_add4(acc + 4 * q, gv[u]);
+            else st<NT>(accv + q, add4(av[u], gv[u]));
         }
     }
 }
 
-template <int U, int W, bool NT, bool ATOMIC>
-__global__ __launch_bounds__(kThreads) void k_accum_flat(RankPtrs accs, const uint16_t *__restrict__ grad,
-                                                         int64_t S, int64_t N, int r0)
+template <int TPB, int U, bool NT, bool ATOMIC>
+__global__ __launch_bounds__(TPB) void k_accum_flat(RankPtrs accs, const uint16_t *__restrict__ grad,
+                                                    int64_t S, int64_t N, int r0, int remap)
 {
     const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
     int64_t valid = N - base;
@@ -233,23 +218,24 @@ __global__ __launch_bounds__(kThreads) void k_accum_flat(RankPtrs accs, const ui
     if (valid <= 0) return;
     float *__restrict__ acc = static_cast<float *>(accs.p[blockIdx.y]);
     const uint16_t *__restrict__ g = grad + base;
-    const int64_t nitem = valid / W;
-    const int tail = static_cast<int>(valid - nitem * W);
+    const int64_t nitem = valid >> 2;
+    const int tail = static_cast<int>(valid & 3);
 
-    const int64_t ntiles = (nitem + kThreads * U - 1) / (kThreads * U);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t t0 = tile * (kThreads * U);
-        if (t0 + kThreads * U <= nitem) accum_tile<U, W, NT, ATOMIC, false>(acc, g, t0 + threadIdx.x, nitem);
-        else accum_tile<U, W, NT, ATOMIC, true>(acc, g, t0 + threadIdx.x, nitem);
+    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
+    const int64_t nslots = slots_of(ntiles, remap);
+    for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
+        const int64_t t0 = tile_of(slot, ntiles, remap) * (TPB * U);
+        if (t0 + TPB * U <= nitem) accum_tile<TPB, U, NT, ATOMIC, false>(acc, g, t0 + threadIdx.x, nitem);
+        else if (t0 < nitem) accum_tile<TPB, U, NT, ATOMIC, true>(acc, g, t0 + threadIdx.x, nitem);
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
-        const int64_t k = nitem * W + threadIdx.x;
+        const int64_t k = 4 * nitem + threadIdx.x;
         add_one<ATOMIC>(acc + k, widen_one(g[k]));
     }
 }
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void k_reset_flat(RankPtrs accs, int64_t S, int64_t N, int r0)
+template <int TPB, int U, bool NT>
+__global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, int64_t N, int r0, int remap)
 {
     const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
     int64_t valid = N - base;
@@ -259,12 +245,13 @@ __global__ __launch_bounds__(kThreads) void k_reset_flat(RankPtrs accs, int64_t 
     const int64_t nvec = valid >> 2;
     const int tail = static_cast<int>(valid & 3);
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    const int64_t ntiles = (nvec + kThreads * U - 1) / (kThreads * U);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t v0 = tile * (kThreads * U) + threadIdx.x;
+    const int64_t ntiles = (nvec + TPB * U - 1) / (TPB * U);
+    const int64_t nslots = slots_of(ntiles, remap);
+    for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
+        const int64_t v0 = tile_of(slot, ntiles, remap) * (TPB * U) + threadIdx.x;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t v = v0 + u * kThreads;
+            const int64_t v = v0 + u * TPB;
             if (v < nvec) st<NT>(reinterpret_cast<f32x4 *>(acc) + v, zero);
         }
     }
@@ -299,22 +286,22 @@ __device__ __forceinline__ int valid_from(const TensorDesc &d, int r, int64_t sl
     return left >= width ? width : (left > 0 ? static_cast<int>(left) : 0);
 }
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
+template <int TPB, int U, bool NT>
+__global__ __launch_bounds__(TPB) void k_gather_batched(BatchTable tb, RankPtrs arenas,
                                                              uint16_t *__restrict__ full, int r0)
 {
     const int r = r0 + static_cast<int>(blockIdx.y);
     const uint16_t *__restrict__ arena = static_cast<const uint16_t *>(arenas.p[blockIdx.y]);
     const int64_t nitem = (tb.arena_elems + 7) >> 3;
-    const int64_t ntiles = (nitem + kThreads * U - 1) / (kThreads * U);
+    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (kThreads * U) + threadIdx.x;
+        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
         u32x4 reg[U];
         uint16_t *dst[U];
         int cnt[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t a = 8 * (q0 + u * kThreads);
+            const int64_t a = 8 * (q0 + u * TPB);
             cnt[u] = 0;
             if (a < tb.arena_elems) {
                 const TensorDesc d = tb.desc[find_tensor(tb, a)];
@@ -329,30 +316,30 @@ __global__ __launch_bounds__(kThreads) void k_gather_batched(BatchTable tb, Rank
             if (cnt[u] == 8) {
                 st_u128_unaligned<NT>(dst[u], reg[u]);
             } else if (cnt[u] > 0) {
-                const uint16_t *s = arena + 8 * (q0 + u * kThreads);
+                const uint16_t *s = arena + 8 * (q0 + u * TPB);
                 for (int k = 0; k < cnt[u]; ++k) dst[u][k] = s[k];
             }
         }
     }
 }
 
-template <int U, bool NT, bool ATOMIC>
-__global__ __launch_bounds__(kThreads) void k_accum_batched(BatchTable tb, RankPtrs accs,
+template <int TPB, int U, bool NT, bool ATOMIC>
+__global__ __launch_bounds__(TPB) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                             const uint16_t *__restrict__ grad, int r0)
 {
     const int r = r0 + static_cast<int>(blockIdx.y);
     float *__restrict__ arena = static_cast<float *>(accs.p[blockIdx.y]);
     const int64_t nitem = (tb.arena_elems + 3) >> 2;
-    const int64_t ntiles = (nitem + kThreads * U - 1) / (kThreads * U);
+    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (kThreads * U) + threadIdx.x;
+        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
         u32x2 gv[U];
         f32x4 av[U];
         const uint16_t *gp[U];
         int cnt[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t a = 4 * (q0 + u * kThreads);
+            const int64_t a = 4 * (q0 + u * TPB);
             cnt[u] = 0;
             if (a < tb.arena_elems) {
                 const TensorDesc d = tb.desc[find_tensor(tb, a)];
@@ -367,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void k_accum_batched(BatchTable tb, RankP
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float *a = arena + 4 * (q0 + u * kThreads);
+            float *a = arena + 4 * (q0 + u * TPB);
             if (cnt[u] == 4) {
                 if constexpr (ATOMIC) {
                     unsafeAtomicAdd(a + 0, widen_lo(gv[u].x));
@@ -389,19 +376,19 @@ __global__ __launch_bounds__(kThreads) void k_accum_batched(BatchTable tb, RankP
     }
 }
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void k_reset_batched(BatchTable tb, RankPtrs accs, int r0)
+template <int TPB, int U, bool NT>
+__global__ __launch_bounds__(TPB) void k_reset_batched(BatchTable tb, RankPtrs accs, int r0)
 {
     const int r = r0 + static_cast<int>(blockIdx.y);
     float *__restrict__ arena = static_cast<float *>(accs.p[blockIdx.y]);
     const int64_t nitem = (tb.arena_elems + 3) >> 2;
-    const int64_t ntiles = (nitem + kThreads * U - 1) / (kThreads * U);
+    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (kThreads * U) + threadIdx.x;
+        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t a = 4 * (q0 + u * kThreads);
+            const int64_t a = 4 * (q0 + u * TPB);
             if (a < tb.arena_elems) {
                 const TensorDesc d = tb.desc[find_tensor(tb, a)];
                 const int cnt = valid_from(d, r, a - d.shard_off, 4);
@@ -414,20 +401,20 @@ __global__ __launch_bounds__(kThreads) void k_reset_batched(BatchTable tb, RankP
 }
 
 // ----------------------------------------------------------------------------------- probe
-template <int U>
-__global__ __launch_bounds__(kThreads) void k_probe_copy(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+template <int TPB, int U>
+__global__ __launch_bounds__(TPB) void k_probe_copy(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
                                                          int64_t nvec)
 {
-    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * (TPB * U) + threadIdx.x;
     u32x4 reg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t v = v0 + u * kThreads;
+        const int64_t v = v0 + u * TPB;
         if (v < nvec) reg[u] = __builtin_nontemporal_load(src + v);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t v = v0 + u * kThreads;
+        const int64_t v = v0 + u * TPB;
         if (v < nvec) __builtin_nontemporal_store(reg[u], dst + v);
     }
 }

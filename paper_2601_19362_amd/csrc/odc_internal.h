@@ -68,13 +68,22 @@ inline unsigned grid_x_for(int64_t items, int per_block, int cap)
     return static_cast<unsigned>(tiles);
 }
 
-// Launch knobs (process-wide, diagnostics only).
+// Launch knobs (process-wide, diagnostics only; results never depend on them).  The defaults
+// are the best point of a sweep over threads x unroll x tile order on the 1.5B-, 7B- and
+// 32B-shaped layers: one wavefront per workgroup and one 16-byte item per lane for the two
+// read-write streams (the chip then sweeps one compact, steadily advancing address window,
+// which HBM serves best), four wavefronts per workgroup for the write-only reset, which is
+// otherwise limited by the workgroup launch rate.
 struct Tuning {
-    int gather_unroll = 4;   // 16-byte vectors per thread in the gather kernels (1, 2, 4, 8)
-    int accum_unroll = 4;    // accumulator vectors per thread (1, 2, 4, 8)
-    int accum_width = 4;     // elements per accumulate work item: 4 or 8
-    int nontemporal = 1;     // 1: streaming loads/stores carry the non-temporal hint
-    int max_grid_x = 0;      // 0: one block per tile; > 0: cap and loop (persistent style)
+    int gather_threads = 64;   // workgroup size of the flat kernels: 64, 128 or 256
+    int accum_threads = 64;
+    int reset_threads = 256;
+    int gather_unroll = 1;     // work items per thread and tile: 1, 2 or 4
+    int accum_unroll = 1;
+    int reset_unroll = 1;
+    int nontemporal = 1;       // 1: streaming loads/stores carry the non-temporal hint
+    int max_grid_x = 0;        // 0: one workgroup per tile; > 0: cap and loop (persistent style)
+    int tile_remap = 0;        // 1: each XCD sweeps its own contiguous eighth of the tiles
 };
 Tuning &tuning();
 

@@ -18,31 +18,42 @@ RankPtrs pack(const void *const *ptrs, int nr)
     return rp;
 }
 
+// Grid for `items` work items at TPB * U items per tile.  With tile remapping the x extent
+// is rounded up to a multiple of 8 (one slot per XCD part) and never capped.
 dim3 grid_for(int64_t items, int per_block, int nr)
 {
-    return dim3(grid_x_for(items, per_block, tuning().max_grid_x), static_cast<unsigned>(nr), 1);
+    const Tuning &t = tuning();
+    unsigned gx = grid_x_for(items, per_block, t.tile_remap ? 0 : t.max_grid_x);
+    if (t.tile_remap && gx <= 0x7FFFFFF0u) gx = (gx + 7u) & ~7u;
+    return dim3(gx, static_cast<unsigned>(nr), 1);
 }
 
 int finish() { return static_cast<int>(hipGetLastError()); }
 
-// Dispatch a runtime (unroll, non-temporal) pair to the matching instantiation.
-#define ODC_DISPATCH_U_NT(UN, NTF, CALL)                                  \
-    do {                                                                  \
-        if (NTF) {                                                        \
-            switch (UN) {                                                 \
-                case 1: { constexpr int U_ = 1; constexpr bool NT_ = true; CALL; } break;  \
-                case 2: { constexpr int U_ = 2; constexpr bool NT_ = true; CALL; } break;  \
-                case 8: { constexpr int U_ = 8; constexpr bool NT_ = true; CALL; } break;  \
-                default: { constexpr int U_ = 4; constexpr bool NT_ = true; CALL; } break; \
-            }                                                             \
-        } else {                                                          \
-            switch (UN) {                                                 \
-                case 1: { constexpr int U_ = 1; constexpr bool NT_ = false; CALL; } break;  \
-                case 2: { constexpr int U_ = 2; constexpr bool NT_ = false; CALL; } break;  \
-                case 8: { constexpr int U_ = 8; constexpr bool NT_ = false; CALL; } break;  \
-                default: { constexpr int U_ = 4; constexpr bool NT_ = false; CALL; } break; \
-            }                                                             \
-        }                                                                 \
+// Dispatch runtime (threads, unroll, non-temporal) to the matching instantiation.  Inside
+// CALL the chosen values are the constants TPB_, U_ and NT_.
+#define ODC_DISPATCH_NT(NTF, CALL)                       \
+    do {                                                 \
+        if (NTF) { constexpr bool NT_ = true; CALL; }    \
+        else { constexpr bool NT_ = false; CALL; }       \
+    } while (0)
+
+#define ODC_DISPATCH_U(UN, NTF, CALL)                                           \
+    do {                                                                        \
+        switch (UN) {                                                           \
+            case 1: { constexpr int U_ = 1; ODC_DISPATCH_NT(NTF, CALL); } break; \
+            case 2: { constexpr int U_ = 2; ODC_DISPATCH_NT(NTF, CALL); } break; \
+            default: { constexpr int U_ = 4; ODC_DISPATCH_NT(NTF, CALL); } break; \
+        }                                                                       \
+    } while (0)
+
+#define ODC_DISPATCH(TPBV, UN, NTF, CALL)                                                  \
+    do {                                                                                   \
+        switch (TPBV) {                                                                    \
+            case 64: { constexpr int TPB_ = 64; ODC_DISPATCH_U(UN, NTF, CALL); } break;     \
+            case 128: { constexpr int TPB_ = 128; ODC_DISPATCH_U(UN, NTF, CALL); } break;   \
+            default: { constexpr int TPB_ = 256; ODC_DISPATCH_U(UN, NTF, CALL); } break;    \
+        }                                                                                  \
     } while (0)
 
 }  // namespace
@@ -53,9 +64,9 @@ int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int6
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_U_NT(t.gather_unroll, t.nontemporal != 0,
-                      (k_gather_flat<U_, NT_><<<grid_for((S >> 3) + 1, kThreads * U_, nr), kThreads, 0, s>>>(
-                          rp, static_cast<uint16_t *>(full), S, N, r0)));
+    ODC_DISPATCH(t.gather_threads, t.gather_unroll, t.nontemporal != 0,
+                 (k_gather_flat<TPB_, U_, NT_><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
     return finish();
 }
 
@@ -67,17 +78,13 @@ int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     if (atomic) {
-        ODC_DISPATCH_U_NT(t.accum_unroll, false,
-                          (k_accum_flat<U_, 4, NT_, true><<<grid_for((S >> 2) + 1, kThreads * U_, nr), kThreads, 0, s>>>(
-                              rp, g, S, N, r0)));
-    } else if (t.accum_width == 8) {
-        ODC_DISPATCH_U_NT(t.accum_unroll, t.nontemporal != 0,
-                          (k_accum_flat<U_, 8, NT_, false><<<grid_for((S >> 3) + 1, kThreads * U_, nr), kThreads, 0, s>>>(
-                              rp, g, S, N, r0)));
+        ODC_DISPATCH(t.accum_threads, t.accum_unroll, false,
+                     (k_accum_flat<TPB_, U_, NT_, true><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         rp, g, S, N, r0, t.tile_remap)));
     } else {
-        ODC_DISPATCH_U_NT(t.accum_unroll, t.nontemporal != 0,
-                          (k_accum_flat<U_, 4, NT_, false><<<grid_for((S >> 2) + 1, kThreads * U_, nr), kThreads, 0, s>>>(
-                              rp, g, S, N, r0)));
+        ODC_DISPATCH(t.accum_threads, t.accum_unroll, t.nontemporal != 0,
+                     (k_accum_flat<TPB_, U_, NT_, false><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         rp, g, S, N, r0, t.tile_remap)));
     }
     return finish();
 }
@@ -87,9 +94,16 @@ int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, v
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_U_NT(t.accum_unroll, t.nontemporal != 0,
-                      (k_reset_flat<U_, NT_><<<grid_for((S >> 2) + 1, kThreads * U_, nr), kThreads, 0, s>>>(rp, S, N, r0)));
+    ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
+                 (k_reset_flat<TPB_, U_, NT_><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     rp, S, N, r0, t.tile_remap)));
     return finish();
+}
+
+// The batched kernels always use 256-thread workgroups and plain tile order.
+static dim3 batched_grid(int64_t items, int per_block, int nr)
+{
+    return dim3(grid_x_for(items, per_block, tuning().max_grid_x), static_cast<unsigned>(nr), 1);
 }
 
 int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr, void *full,
@@ -98,9 +112,10 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_U_NT(t.gather_unroll, t.nontemporal != 0,
-                      (k_gather_batched<U_, NT_><<<grid_for((tb.arena_elems + 7) >> 3, kThreads * U_, nr), kThreads, 0, s>>>(
-                          tb, rp, static_cast<uint16_t *>(full), r0)));
+    constexpr int TPB_ = 256;
+    ODC_DISPATCH_U(t.gather_unroll, t.nontemporal != 0,
+                   (k_gather_batched<TPB_, U_, NT_><<<batched_grid((tb.arena_elems + 7) >> 3, TPB_ * U_, nr), TPB_, 0, s>>>(
+                       tb, rp, static_cast<uint16_t *>(full), r0)));
     return finish();
 }
 
@@ -111,14 +126,15 @@ int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
+    constexpr int TPB_ = 256;
     if (atomic) {
-        ODC_DISPATCH_U_NT(t.accum_unroll, false,
-                          (k_accum_batched<U_, NT_, true><<<grid_for((tb.arena_elems + 3) >> 2, kThreads * U_, nr), kThreads, 0, s>>>(
-                              tb, rp, g, r0)));
+        ODC_DISPATCH_U(t.accum_unroll, false,
+                       (k_accum_batched<TPB_, U_, NT_, true><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(
+                           tb, rp, g, r0)));
     } else {
-        ODC_DISPATCH_U_NT(t.accum_unroll, t.nontemporal != 0,
-                          (k_accum_batched<U_, NT_, false><<<grid_for((tb.arena_elems + 3) >> 2, kThreads * U_, nr), kThreads, 0, s>>>(
-                              tb, rp, g, r0)));
+        ODC_DISPATCH_U(t.accum_unroll, t.nontemporal != 0,
+                       (k_accum_batched<TPB_, U_, NT_, false><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(
+                           tb, rp, g, r0)));
     }
     return finish();
 }
@@ -128,8 +144,9 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_U_NT(t.accum_unroll, t.nontemporal != 0,
-                      (k_reset_batched<U_, NT_><<<grid_for((tb.arena_elems + 3) >> 2, kThreads * U_, nr), kThreads, 0, s>>>(tb, rp, r0)));
+    constexpr int TPB_ = 256;
+    ODC_DISPATCH_U(t.reset_unroll, t.nontemporal != 0,
+                   (k_reset_batched<TPB_, U_, NT_><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(tb, rp, r0)));
     return finish();
 }
 
@@ -137,9 +154,10 @@ int launch_probe_copy(void *dst, const void *src, int64_t bytes, void *stream)
 {
     const int64_t nvec = bytes >> 4;
     if (nvec == 0) return 0;
-    constexpr int U = 4;
-    const int64_t blocks = (nvec + kThreads * U - 1) / (kThreads * U);
-    k_probe_copy<U><<<dim3(static_cast<unsigned>(blocks)), kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+    constexpr int TPB = 256, U = 4;
+    const int64_t blocks = (nvec + TPB * U - 1) / (TPB * U);
+    if (blocks > 0x7FFFFFFF) return static_cast<int>(hipErrorInvalidValue);
+    k_probe_copy<TPB, U><<<dim3(static_cast<unsigned>(blocks)), TPB, 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
     return finish();
 }

@@ -5,7 +5,7 @@
 // rank buffer is its own exactly-sized heap block, so any access outside the valid range of
 // a buffer is reported.  The test compares the outputs with the CPU oracle.
 //
-// usage: emu <dir> <op> <R> <unroll> <nt> <width> <atomic> <grid_cap>
+// usage: emu <dir> <op> <R> <threads> <unroll> <nt> <remap> <atomic> <grid_cap>
 //   dir holds numel.i64 [T]; arenas.u16 [R*arena] (gather); full.u16 [full] (gather in/out);
 //   grad.u16 [full] and acc.f32 [R*arena] (accum / reset, in/out)
 #include "hip_shim.h"
@@ -46,14 +46,14 @@ void write_file(const std::string &path, const T *p, size_t n)
 }
 
 template <typename F>
-void run_grid(unsigned gx, unsigned gy, F &&kernel)
+void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
 {
     gridDim.x = gx;
     gridDim.y = gy;
-    blockDim.x = 256;
+    blockDim.x = tpb;
     for (unsigned y = 0; y < gy; ++y)
         for (unsigned x = 0; x < gx; ++x)
-            for (unsigned t = 0; t < 256; ++t) {
+            for (unsigned t = 0; t < tpb; ++t) {
                 blockIdx.x = x;
                 blockIdx.y = y;
                 threadIdx.x = t;
@@ -61,36 +61,50 @@ void run_grid(unsigned gx, unsigned gy, F &&kernel)
             }
 }
 
-#define EMU_DISPATCH(UN, NTF, CALL)                                                       \
-    do {                                                                                  \
-        if (NTF) {                                                                        \
-            switch (UN) {                                                                 \
-                case 1: { constexpr int U_ = 1; constexpr bool NT_ = true; CALL; } break;  \
-                case 2: { constexpr int U_ = 2; constexpr bool NT_ = true; CALL; } break;  \
-                case 8: { constexpr int U_ = 8; constexpr bool NT_ = true; CALL; } break;  \
-                default: { constexpr int U_ = 4; constexpr bool NT_ = true; CALL; } break; \
-            }                                                                             \
-        } else {                                                                          \
-            switch (UN) {                                                                 \
-                case 1: { constexpr int U_ = 1; constexpr bool NT_ = false; CALL; } break;  \
-                case 2: { constexpr int U_ = 2; constexpr bool NT_ = false; CALL; } break;  \
-                case 8: { constexpr int U_ = 8; constexpr bool NT_ = false; CALL; } break;  \
-                default: { constexpr int U_ = 4; constexpr bool NT_ = false; CALL; } break; \
-            }                                                                             \
-        }                                                                                 \
+#define EMU_NT(NTF, CALL)                             \
+    do {                                              \
+        if (NTF) { constexpr bool NT_ = true; CALL; } \
+        else { constexpr bool NT_ = false; CALL; }    \
     } while (0)
+
+#define EMU_U(UN, NTF, CALL)                                            \
+    do {                                                                \
+        switch (UN) {                                                   \
+            case 1: { constexpr int U_ = 1; EMU_NT(NTF, CALL); } break;  \
+            case 2: { constexpr int U_ = 2; EMU_NT(NTF, CALL); } break;  \
+            default: { constexpr int U_ = 4; EMU_NT(NTF, CALL); } break; \
+        }                                                               \
+    } while (0)
+
+#define EMU_DISPATCH(TPBV, UN, NTF, CALL)                                         \
+    do {                                                                          \
+        switch (TPBV) {                                                           \
+            case 64: { constexpr int TPB_ = 64; EMU_U(UN, NTF, CALL); } break;     \
+            case 128: { constexpr int TPB_ = 128; EMU_U(UN, NTF, CALL); } break;   \
+            default: { constexpr int TPB_ = 256; EMU_U(UN, NTF, CALL); } break;    \
+        }                                                                         \
+    } while (0)
+
+// x extent as the launcher computes it
+unsigned gx_for(int64_t items, int per_block, int cap, int remap)
+{
+    unsigned gx = odc::grid_x_for(items, per_block, remap ? 0 : cap);
+    if (remap) gx = (gx + 7u) & ~7u;
+    return gx;
+}
 
 }  // namespace
 
 int main(int argc, char **argv)
 {
-    if (argc != 9) {
-        std::fprintf(stderr, "usage: emu dir op R unroll nt width atomic grid_cap\n");
+    if (argc != 10) {
+        std::fprintf(stderr, "usage: emu dir op R threads unroll nt remap atomic grid_cap\n");
         return 2;
     }
     const std::string dir = argv[1], op = argv[2];
-    const int R = std::atoi(argv[3]), unroll = std::atoi(argv[4]), nt = std::atoi(argv[5]);
-    const int width = std::atoi(argv[6]), atomic = std::atoi(argv[7]), cap = std::atoi(argv[8]);
+    const int R = std::atoi(argv[3]), threads = std::atoi(argv[4]), unroll = std::atoi(argv[5]);
+    const int nt = std::atoi(argv[6]), remap = std::atoi(argv[7]), atomic = std::atoi(argv[8]);
+    const int cap = std::atoi(argv[9]);
     using namespace odc;
 
     std::vector<int64_t> numel = read_file<int64_t>(dir + "/numel.i64");
@@ -125,13 +139,15 @@ int main(int argc, char **argv)
             RankPtrs rp{};
             for (int k = 0; k < nr; ++k) rp.p[k] = bufs[r0 + k];
             if (flat) {
-                EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 3) + 1, 256 * U_, cap), nr, [&] {
-                                 k_gather_flat<U_, NT_>(rp, full, S, N, r0);
+                EMU_DISPATCH(threads, unroll, nt,
+                             run_grid(TPB_, gx_for((S >> 3) + 1, TPB_ * U_, cap, remap), nr, [&] {
+                                 k_gather_flat<TPB_, U_, NT_>(rp, full, S, N, r0, remap);
                              }));
             } else {
-                EMU_DISPATCH(unroll, nt,
-                             run_grid(grid_x_for((tb.arena_elems + 7) >> 3, 256 * U_, cap), nr,
-                                      [&] { k_gather_batched<U_, NT_>(tb, rp, full, r0); }));
+                constexpr int TPB_ = 256;
+                EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 7) >> 3, TPB_ * U_, cap, 0), nr, [&] {
+                          k_gather_batched<TPB_, U_, NT_>(tb, rp, full, r0);
+                      }));
             }
         }
         write_file(dir + "/full.out", full, full_n);
@@ -143,10 +159,9 @@ int main(int argc, char **argv)
     if (op == "accum" || op == "reset") {
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;
-        std::vector<uint16_t> grad_in;
         uint16_t *grad = nullptr;
         if (op == "accum") {
-            grad_in = read_file<uint16_t>(dir + "/grad.u16");
+            std::vector<uint16_t> grad_in = read_file<uint16_t>(dir + "/grad.u16");
             if (grad_in.size() != full_n) return 4;
             grad = static_cast<uint16_t *>(std::malloc(full_n * 2));
             std::memcpy(grad, grad_in.data(), full_n * 2);
@@ -162,35 +177,37 @@ int main(int argc, char **argv)
             for (int k = 0; k < nr; ++k) rp.p[k] = bufs[r0 + k];
             if (op == "reset") {
                 if (flat) {
-                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr,
-                                                      [&] { k_reset_flat<U_, NT_>(rp, S, N, r0); }));
+                    EMU_DISPATCH(threads, unroll, nt,
+                                 run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr,
+                                          [&] { k_reset_flat<TPB_, U_, NT_>(rp, S, N, r0, remap); }));
                 } else {
-                    EMU_DISPATCH(unroll, nt,
-                                 run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
-                                          [&] { k_reset_batched<U_, NT_>(tb, rp, r0); }));
+                    constexpr int TPB_ = 256;
+                    EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr,
+                                               [&] { k_reset_batched<TPB_, U_, NT_>(tb, rp, r0); }));
                 }
             } else if (flat) {
                 if (atomic) {
-                    EMU_DISPATCH(unroll, 0, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr, [&] {
-                                     k_accum_flat<U_, 4, NT_, true>(rp, grad, S, N, r0);
-                                 }));
-                } else if (width == 8) {
-                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 3) + 1, 256 * U_, cap), nr, [&] {
-                                     k_accum_flat<U_, 8, NT_, false>(rp, grad, S, N, r0);
+                    EMU_DISPATCH(threads, unroll, 0,
+                                 run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr, [&] {
+                                     k_accum_flat<TPB_, U_, NT_, true>(rp, grad, S, N, r0, remap);
                                  }));
                 } else {
-                    EMU_DISPATCH(unroll, nt, run_grid(grid_x_for((S >> 2) + 1, 256 * U_, cap), nr, [&] {
-                                     k_accum_flat<U_, 4, NT_, false>(rp, grad, S, N, r0);
+                    EMU_DISPATCH(threads, unroll, nt,
+                                 run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr, [&] {
+                                     k_accum_flat<TPB_, U_, NT_, false>(rp, grad, S, N, r0, remap);
                                  }));
                 }
-            } else if (atomic) {
-                EMU_DISPATCH(unroll, 0,
-                             run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
-                                      [&] { k_accum_batched<U_, NT_, true>(tb, rp, grad, r0); }));
             } else {
-                EMU_DISPATCH(unroll, nt,
-                             run_grid(grid_x_for((tb.arena_elems + 3) >> 2, 256 * U_, cap), nr,
-                                      [&] { k_accum_batched<U_, NT_, false>(tb, rp, grad, r0); }));
+                constexpr int TPB_ = 256;
+                if (atomic) {
+                    EMU_U(unroll, 0, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr, [&] {
+                              k_accum_batched<TPB_, U_, NT_, true>(tb, rp, grad, r0);
+                          }));
+                } else {
+                    EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr, [&] {
+                              k_accum_batched<TPB_, U_, NT_, false>(tb, rp, grad, r0);
+                          }));
+                }
             }
         }
         std::vector<float> out(arena * static_cast<size_t>(R));

@@ -90,20 +90,27 @@ def test_stress_config(oracle):
 
 
 @pytest.mark.parametrize("knobs", [
-    dict(gather_unroll=1, accum_unroll=1, nontemporal=0, accum_width=4, max_grid_x=0),
-    dict(gather_unroll=2, accum_unroll=2, nontemporal=1, accum_width=8, max_grid_x=0),
-    dict(gather_unroll=8, accum_unroll=8, nontemporal=1, accum_width=4, max_grid_x=7),
-    dict(gather_unroll=4, accum_unroll=8, nontemporal=0, accum_width=8, max_grid_x=512),
+    dict(gather_threads=64, accum_threads=64, reset_threads=64, gather_unroll=1, accum_unroll=1, reset_unroll=1),
+    dict(gather_threads=128, accum_threads=128, reset_threads=128, gather_unroll=2, accum_unroll=2, reset_unroll=2,
+         nontemporal=0),
+    dict(gather_threads=256, accum_threads=256, reset_threads=256, gather_unroll=4, accum_unroll=4, reset_unroll=4,
+         max_grid_x=7),
+    dict(gather_threads=64, accum_threads=64, reset_threads=256, gather_unroll=1, accum_unroll=1, reset_unroll=1,
+         tile_remap=1),
+    dict(gather_threads=256, accum_threads=128, reset_threads=64, gather_unroll=2, accum_unroll=4, reset_unroll=4,
+         tile_remap=1, nontemporal=0),
 ])
 def test_results_do_not_depend_on_launch_knobs(oracle, knobs):
+    """Every launch configuration gives the same bits."""
+    neutral = dict(nontemporal=1, max_grid_x=0, tile_remap=0)
     try:
-        for k, v in knobs.items():
+        for k, v in {**neutral, **knobs}.items():
             odc.tune(k, v)
         run_case(oracle, [2_000_003], 4, [(0, 0), (1, 0), (1, 1)], seed=77)
+        run_case(oracle, [1_000_000], 8, [(0, 0)], seed=79)
         run_case(oracle, [30000, 17, 2048, 2049, 100_001], 5, [(0, 0), (4, 2)], seed=78)
     finally:
-        for k, v in dict(gather_unroll=4, accum_unroll=4, nontemporal=1, accum_width=4, max_grid_x=0).items():
-            odc.tune(k, v)
+        odc.reset_tuning()
 
 
 def test_special_values(oracle):

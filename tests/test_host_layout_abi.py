@@ -147,8 +147,11 @@ def test_probe_and_tune_argument_errors():
     assert lib.odc_tune(b"gather_unroll", 3) == odc.ODC_ERR_INVALID_ARG
     assert lib.odc_tune(b"no_such_knob", 1) == odc.ODC_ERR_INVALID_ARG
     assert lib.odc_tune(None, 1) == odc.ODC_ERR_INVALID_ARG
-    assert lib.odc_tune(b"gather_unroll", 4) == 0
-    assert lib.odc_tune(b"accum_unroll", 4) == 0
-    assert lib.odc_tune(b"accum_width", 4) == 0
-    assert lib.odc_tune(b"nontemporal", 1) == 0
-    assert lib.odc_tune(b"max_grid_x", 0) == 0
+    assert lib.odc_tune(b"gather_threads", 100) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(b"nontemporal", 2) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(b"max_grid_x", -1) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_tune(b"defaults", 1) == odc.ODC_ERR_INVALID_ARG
+    for knob, value in [(b"gather_threads", 64), (b"accum_threads", 128), (b"reset_threads", 256),
+                        (b"gather_unroll", 1), (b"accum_unroll", 2), (b"reset_unroll", 4),
+                        (b"nontemporal", 0), (b"tile_remap", 1), (b"max_grid_x", 512), (b"defaults", 0)]:
+        assert lib.odc_tune(knob, value) == 0

@@ -45,9 +45,9 @@ def placement(numel, R):
     return S, so, fo, so[-1] + S[-1], fo[-1] + numel[-1]
 
 
-def run(emu, d, op, R, unroll=4, nt=1, width=4, atomic=0, cap=0):
-    p = subprocess.run([emu, str(d), op, str(R), str(unroll), str(nt), str(width), str(atomic),
-                        str(cap)], capture_output=True, text=True,
+def run(emu, d, op, R, threads=256, unroll=4, nt=1, remap=0, atomic=0, cap=0):
+    p = subprocess.run([emu, str(d), op, str(R), str(threads), str(unroll), str(nt), str(remap),
+                        str(atomic), str(cap)], capture_output=True, text=True,
                        env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0"})
     assert p.returncode == 0, p.stderr[-3000:]
 
@@ -76,13 +76,14 @@ CASES = [
 
 
 @pytest.mark.parametrize("numel,R", CASES)
-@pytest.mark.parametrize("unroll,nt,cap", [(4, 1, 0), (1, 0, 3), (8, 1, 1)])
-def test_emulated_gather(oracle, emu, tmp_path, numel, R, unroll, nt, cap):
+@pytest.mark.parametrize("threads,unroll,nt,remap,cap", [(256, 4, 1, 0, 0), (64, 1, 0, 0, 3), (128, 2, 1, 1, 0),
+                                                         (64, 1, 1, 1, 0), (256, 2, 1, 0, 1)])
+def test_emulated_gather(oracle, emu, tmp_path, numel, R, threads, unroll, nt, remap, cap):
     S, so, fo, arena, full_n, arenas, flats = make_case(oracle, numel, R, seed=1)
     np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
     np.concatenate(arenas).tofile(tmp_path / "arenas.u16")
     np.full(full_n, 0xBEEF, dtype=np.uint16).tofile(tmp_path / "full.u16")
-    run(emu, tmp_path, "gather", R, unroll=unroll, nt=nt, cap=cap)
+    run(emu, tmp_path, "gather", R, threads=threads, unroll=unroll, nt=nt, remap=remap, cap=cap)
     got = np.fromfile(tmp_path / "full.out", dtype=np.uint16)
     want = np.full(full_n, 0xBEEF, dtype=np.uint16)
     oracle.gather_batched(arenas, numel, so, fo, want)
@@ -92,14 +93,15 @@ def test_emulated_gather(oracle, emu, tmp_path, numel, R, unroll, nt, cap):
 
 
 @pytest.mark.parametrize("numel,R", CASES)
-@pytest.mark.parametrize("unroll,nt,width,atomic,cap", [(4, 1, 4, 0, 0), (2, 0, 8, 0, 2), (8, 1, 4, 1, 0),
-                                                        (1, 1, 8, 0, 0)])
-def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, unroll, nt, width, atomic, cap):
+@pytest.mark.parametrize("threads,unroll,nt,remap,atomic,cap", [(256, 4, 1, 0, 0, 0), (64, 1, 1, 0, 0, 0),
+                                                                (128, 2, 0, 1, 0, 0), (64, 4, 1, 0, 1, 2),
+                                                                (64, 1, 1, 1, 0, 0)])
+def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, threads, unroll, nt, remap, atomic, cap):
     S, so, fo, arena, full_n = placement(numel, R)
     np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
     acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
     np.concatenate(acc).tofile(tmp_path / "acc.f32")
-    run(emu, tmp_path, "reset", R, unroll=unroll, nt=nt, cap=cap)
+    run(emu, tmp_path, "reset", R, threads=threads, unroll=unroll, nt=nt, remap=remap, cap=cap)
     got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
     oracle.reset_batched(acc, numel, so)
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
@@ -107,7 +109,7 @@ def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, unroll, 
         g = inputs.normal_bf16(full_n, 1e-2, seed=(2, k))
         g.tofile(tmp_path / "grad.u16")
         got.tofile(tmp_path / "acc.f32")
-        run(emu, tmp_path, "accum", R, unroll=unroll, nt=nt, width=width, atomic=atomic, cap=cap)
+        run(emu, tmp_path, "accum", R, threads=threads, unroll=unroll, nt=nt, remap=remap, atomic=atomic, cap=cap)
         got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
         oracle.accumulate_batched(g, acc, numel, so, fo)
         assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
