@@ -49,16 +49,16 @@ int upload_table(odc_layout_t *L)
     if (L->host.T == 1) return ODC_OK;  // flat kernels need no table
     const odc::HostLayout &H = L->host;
     const size_t T = static_cast<size_t>(H.T);
-    const size_t off_bytes = T * sizeof(int64_t);
+    // one blob: descriptors (8-byte aligned data first), then the two tile indices
     const size_t desc_bytes = T * sizeof(odc::TensorDesc);
     const size_t chunk_bytes = H.chunk_first.size() * sizeof(int32_t);
-    const size_t total = off_bytes + desc_bytes + chunk_bytes;
+    const size_t full_chunk_bytes = H.full_chunk_first.size() * sizeof(int32_t);
+    const size_t total = desc_bytes + chunk_bytes + full_chunk_bytes;
     char *staging = new (std::nothrow) char[total];
     if (!staging) return ODC_ERR_NOMEM;
-    int64_t *offs = reinterpret_cast<int64_t *>(staging);
-    for (size_t t = 0; t < T; ++t) offs[t] = H.desc[t].shard_off;
-    std::memcpy(staging + off_bytes, H.desc.data(), desc_bytes);
-    std::memcpy(staging + off_bytes + desc_bytes, H.chunk_first.data(), chunk_bytes);
+    std::memcpy(staging, H.desc.data(), desc_bytes);
+    std::memcpy(staging + desc_bytes, H.chunk_first.data(), chunk_bytes);
+    std::memcpy(staging + desc_bytes + chunk_bytes, H.full_chunk_first.data(), full_chunk_bytes);
     e = hipMalloc(&L->d_blob, total);
     if (e == hipSuccess) e = hipMemcpy(L->d_blob, staging, total, hipMemcpyHostToDevice);
     delete[] staging;
@@ -68,10 +68,11 @@ int upload_table(odc_layout_t *L)
         return hip_fail(e);
     }
     char *d = static_cast<char *>(L->d_blob);
-    L->table.shard_off = reinterpret_cast<const int64_t *>(d);
-    L->table.desc = reinterpret_cast<const odc::TensorDesc *>(d + off_bytes);
-    L->table.chunk_first = reinterpret_cast<const int32_t *>(d + off_bytes + desc_bytes);
+    L->table.desc = reinterpret_cast<const odc::TensorDesc *>(d);
+    L->table.chunk_first = reinterpret_cast<const int32_t *>(d + desc_bytes);
+    L->table.full_chunk_first = reinterpret_cast<const int32_t *>(d + desc_bytes + chunk_bytes);
     L->table.arena_elems = H.arena_elems;
+    L->table.full_elems = H.full_elems;
     L->table.T = H.T;
     return ODC_OK;
 }
@@ -283,6 +284,9 @@ int odc_tune(const char *knob, int value)
     else if (!std::strcmp(knob, "nontemporal") && flag_ok) t.nontemporal = value;
     else if (!std::strcmp(knob, "tile_remap") && flag_ok) t.tile_remap = value;
     else if (!std::strcmp(knob, "max_grid_x") && value >= 0) t.max_grid_x = value;
+    else if (!std::strcmp(knob, "batch_rank_group") &&
+             (value == 0 || value == 1 || value == 2 || value == 4 || value == 8))
+        t.batch_rank_group = value;
     else return ODC_ERR_INVALID_ARG;
     return ODC_OK;
 }

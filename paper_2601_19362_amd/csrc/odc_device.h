@@ -38,24 +38,37 @@ struct RankPtrs {
     void *p[kRanksPerLaunch];
 };
 
+// Every data pointer in these kernels points to device (global) memory.  Pointers that reach
+// a lane through LDS or a per-lane table lookup lose that information and would be accessed
+// with slower generic-address instructions, so every access goes through a pointer that is
+// explicitly in the global address space.  (On the host, in the CPU emulation build, the
+// qualifier is empty.)
+#ifdef __HIP_DEVICE_COMPILE__
+#define ODC_GLOBAL __attribute__((address_space(1)))
+#else
+#define ODC_GLOBAL
+#endif
+
 template <bool NT, typename V>
 __device__ __forceinline__ V ld(const V *p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
+    const ODC_GLOBAL V *q = (const ODC_GLOBAL V *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
 }
 
 template <bool NT, typename V>
 __device__ __forceinline__ void st(V *p, V v)
 {
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    ODC_GLOBAL V *q = (ODC_GLOBAL V *)p;
+    if constexpr (NT) __builtin_nontemporal_store(v, q);
+    else *q = v;
 }
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld_u128_unaligned(const uint16_t *p)
 {
-    const u32x4_a2 *q = reinterpret_cast<const u32x4_a2 *>(p);
+    const ODC_GLOBAL u32x4_a2 *q = (const ODC_GLOBAL u32x4_a2 *)p;
     if constexpr (NT) return __builtin_nontemporal_load(q);
     else return *q;
 }
@@ -63,18 +76,16 @@ __device__ __forceinline__ u32x4 ld_u128_unaligned(const uint16_t *p)
 template <bool NT>
 __device__ __forceinline__ u32x2 ld_u64_unaligned(const uint16_t *p)
 {
-    const u32x2_a2 *q = reinterpret_cast<const u32x2_a2 *>(p);
+    const ODC_GLOBAL u32x2_a2 *q = (const ODC_GLOBAL u32x2_a2 *)p;
     if constexpr (NT) return __builtin_nontemporal_load(q);
     else return *q;
 }
 
-template <bool NT>
-__device__ __forceinline__ void st_u128_unaligned(uint16_t *p, u32x4 v)
-{
-    u32x4_a2 *q = reinterpret_cast<u32x4_a2 *>(p);
-    if constexpr (NT) __builtin_nontemporal_store(v, q);
-    else *q = v;
-}
+// Single elements (heads, tails, ragged ends, pieces of small tensors).
+__device__ __forceinline__ uint16_t ld_u16(const uint16_t *p) { return *(const ODC_GLOBAL uint16_t *)p; }
+__device__ __forceinline__ void st_u16(uint16_t *p, uint16_t v) { *(ODC_GLOBAL uint16_t *)p = v; }
+__device__ __forceinline__ float ld_f32(const float *p) { return *(const ODC_GLOBAL float *)p; }
+__device__ __forceinline__ void st_f32(float *p, float v) { *(ODC_GLOBAL float *)p = v; }
 
 // bf16 -> binary32 is exact: the 16 bits are the high half of the word.
 __device__ __forceinline__ float widen_lo(uint32_t two) { return __uint_as_float(two << 16); }
@@ -85,7 +96,7 @@ template <bool ATOMIC>
 __device__ __forceinline__ void add_one(float *a, float v)
 {
     if constexpr (ATOMIC) unsafeAtomicAdd(a, v);
-    else *a = *a + v;
+    else st_f32(a, ld_f32(a) + v);
 }
 
 // ------------------------------------------------------------------------------------ flat
@@ -155,10 +166,10 @@ __global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *
     }
     if (blockIdx.x == 0) {
         const int t = threadIdx.x;
-        if (t < head) dst[t] = src[t];
+        if (t < head) st_u16(dst + t, ld_u16(src + t));
         if (t < tail) {
             const int64_t k = head + 8 * nvec + t;
-            dst[k] = src[k];
+            st_u16(dst + k, ld_u16(src + k));
         }
     }
 }
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(TPB) void k_accum_flat(RankPtrs accs, const uint16_
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
         const int64_t k = 4 * nitem + threadIdx.x;
-        add_one<ATOMIC>(acc + k, widen_one(g[k]));
+        add_one<ATOMIC>(acc + k, widen_one(ld_u16(g + k)));
     }
 }
 
@@ -255,26 +266,72 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
             if (v < nvec) st<NT>(reinterpret_cast<f32x4 *>(acc) + v, zero);
         }
     }
-    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) acc[4 * nvec + threadIdx.x] = 0.0f;
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) st_f32(acc + 4 * nvec + threadIdx.x, 0.0f);
 }
 
 // --------------------------------------------------------------------------------- batched
-// T tensors in one launch.  The kernels walk each owner's rank arena in aligned work items
-// (8 bf16 for gather, 4 floats for accumulate / reset); every tensor starts at a multiple of
-// 8 arena elements, so a work item never straddles two tensors.  A work item finds its
-// tensor through the coarse chunk index plus a short binary search over the start offsets.
+// T tensors in one launch (the many-small-tensor case).  Work is cut into tiles of an index
+// space in which every tensor starts at a multiple of 8 elements:
+//   accumulate / reset walk the owners' rank arenas (the side that is written), so all
+//     writes are dense, aligned 16-byte vectors.  Every owner's arena has the same tensor
+//     placement, so a workgroup takes one tile and a group of RG owners: the tensor of a
+//     work item is looked up once and used for all RG owners, which also puts RG
+//     independent load pairs per item in flight and brings the scattered gradient reads of
+//     the owners of a small tensor close together in time;
+//   gather walks the full buffer (again the side that is written) and pulls each 16-byte
+//     item from the owner that holds it, so the pieces of a small tensor that come from
+//     many owners still leave as full 16-byte stores of one workgroup.
+// The start offsets of the tensors that intersect a tile are staged in LDS once per
+// workgroup (found through the coarse per-chunk index); each work item then locates its
+// tensor with a binary search in LDS and reads the descriptor from the L2-resident table.
+// A tile that lies inside one tensor skips all of that.
 
-__device__ __forceinline__ int find_tensor(const BatchTable &tb, int64_t a)
+constexpr int kChunkElems = 1 << kChunkShift;
+constexpr int kBatchThreads = 256;
+constexpr int kGatherChunks = 4;  // gather tile: 4 chunks = 4 items of 8 elements per thread
+constexpr int kAccumItems = kChunkElems / (4 * kBatchThreads);  // accumulate tile: 1 chunk
+
+template <int CHUNKS>
+struct TileIndex {
+    static constexpr int kMax = CHUNKS * (kChunkElems / static_cast<int>(kAlignElems)) + 2;
+    int32_t rel[kMax];  // start of each staged tensor relative to the tile start, clamped
+    int t_lo;
+    int n;
+};
+
+// Stage the start offsets of the tensors that intersect tile `tile` (CHUNKS chunks) of the
+// rank-arena space (FULL_SPACE = false) or of the full-buffer space (true).  All threads of
+// the workgroup must call it; it ends with a barrier unless only one tensor is involved.
+template <bool FULL_SPACE, int CHUNKS>
+__device__ __forceinline__ void stage_tile(const BatchTable &tb, int64_t tile, int64_t nchunks,
+                                           TileIndex<CHUNKS> &lds, int &t_lo, int &n)
 {
-    const int64_t c = a >> kChunkShift;
-    int lo = tb.chunk_first[c];
-    int hi = tb.chunk_first[c + 1];
+    const int32_t *first = FULL_SPACE ? tb.full_chunk_first : tb.chunk_first;
+    const int64_t c0 = tile * CHUNKS;
+    const int64_t c1 = c0 + CHUNKS < nchunks ? c0 + CHUNKS : nchunks;
+    t_lo = first[c0];
+    n = first[c1] - t_lo + 1;
+    if (n == 1) return;
+    const int64_t a0 = c0 << kChunkShift;
+    for (int k = threadIdx.x; k < n; k += kBatchThreads) {
+        const TensorDesc &d = tb.desc[t_lo + k];
+        const int64_t rel = (FULL_SPACE ? d.full_off : d.shard_off) - a0;
+        lds.rel[k] = rel < -0x40000000 ? -0x40000000 : (rel > 0x40000000 ? 0x40000000 : static_cast<int32_t>(rel));
+    }
+    __syncthreads();
+}
+
+// Index of the tensor that owns tile-relative element `a_rel`.
+template <int CHUNKS>
+__device__ __forceinline__ int tile_tensor(int t_lo, int n, int a_rel, const TileIndex<CHUNKS> &lds)
+{
+    int lo = 0, hi = n - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (tb.shard_off[mid] <= a) lo = mid;
+        if (lds.rel[mid] <= a_rel) lo = mid;
         else hi = mid - 1;
     }
-    return lo;
+    return t_lo + lo;
 }
 
 // Valid elements of tensor d, owner r, starting at slot `slot`, at most `width`.
@@ -286,115 +343,435 @@ __device__ __forceinline__ int valid_from(const TensorDesc &d, int r, int64_t sl
     return left >= width ? width : (left > 0 ? static_cast<int>(left) : 0);
 }
 
-template <int TPB, int U, bool NT>
-__global__ __launch_bounds__(TPB) void k_gather_batched(BatchTable tb, RankPtrs arenas,
-                                                             uint16_t *__restrict__ full, int r0)
+// ---- gather, full-buffer-major ---------------------------------------------------------
+// Per-tensor record of the gather kernel, staged in LDS for multi-tensor tiles.  Offsets are
+// 32-bit and relative to the tile so that the per-item index arithmetic stays in 32-bit
+// integer instructions (64-bit vector integer math is several times slower on this chip
+// and used to make this kernel ALU-bound).  Tensors of 2^30 elements or more take a generic
+// 64-bit path instead (S = 0 marks them).
+struct GatherRec {
+    int32_t rel;        // full_off - tile start (may be negative: tensor began before the tile)
+    uint32_t S;         // shard elements; 0 = use the generic path
+    uint32_t numel;
+    int64_t shard_off;  // start inside every rank arena
+    int32_t tensor;     // index into the descriptor table (generic path)
+};
+
+__device__ __forceinline__ GatherRec make_gather_rec(const TensorDesc &d, int tensor, int64_t a0)
 {
-    const int r = r0 + static_cast<int>(blockIdx.y);
-    const uint16_t *__restrict__ arena = static_cast<const uint16_t *>(arenas.p[blockIdx.y]);
-    const int64_t nitem = (tb.arena_elems + 7) >> 3;
-    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
-        u32x4 reg[U];
-        uint16_t *dst[U];
-        int cnt[U];
+    GatherRec g;
+    const int64_t lim = int64_t{1} << 30;
+    const int64_t rel = d.full_off - a0;
+    // A tensor that intersects the tile began less than numel elements before it, so a
+    // small tensor's offset always fits; only the ordering matters for the others.
+    const bool small = d.numel < lim && rel > -lim;
+    g.rel = static_cast<int32_t>(rel < -lim ? -lim : (rel > lim ? lim : rel));
+    g.S = small ? static_cast<uint32_t>(d.S) : 0u;
+    g.numel = small ? static_cast<uint32_t>(d.numel) : 0u;
+    g.shard_off = d.shard_off;
+    g.tensor = tensor;
+    return g;
+}
+
+// One-instruction reciprocal (about 1 ulp); the host pass and the CPU emulation divide.
+__device__ __forceinline__ float fast_rcp(float x)
+{
+#ifdef __HIP_DEVICE_COMPILE__
+    return __builtin_amdgcn_rcpf(x);
+#else
+    return 1.0f / x;
+#endif
+}
+
+// floor(j / S) for j < 2^30, S >= 1 and a quotient of at most 2^12 (the owner count): the
+// float estimate is off by at most one, which the two comparisons repair.
+__device__ __forceinline__ uint32_t div_owner(uint32_t j, uint32_t S)
+{
+    uint32_t r = static_cast<uint32_t>(static_cast<float>(j) * fast_rcp(static_cast<float>(S)));
+    const int32_t i = static_cast<int32_t>(j - r * S);  // |i| < 2S < 2^31
+    if (i < 0) --r;
+    else if (static_cast<uint32_t>(i) >= S) ++r;
+    return r;
+}
+
+// Elements of one item that do not all sit in one owner's shard (small tensors, shard
+// boundaries, ragged tensor ends): all element loads first, then one wide store if the item
+// is complete and wholly served by this launch, else element stores.
+template <bool NT>
+__device__ __forceinline__ void gather_pieces(uint32_t r, uint32_t i, uint32_t S, int64_t shard_off, int cnt,
+                                              void *const *base, int r0, int nr, uint16_t *dst)
+{
+    uint32_t e[8];
+    bool mine = true;
+    uint32_t rr = r, ii = i;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t a = 8 * (q0 + u * TPB);
-            cnt[u] = 0;
-            if (a < tb.arena_elems) {
-                const TensorDesc d = tb.desc[find_tensor(tb, a)];
-                const int64_t slot = a - d.shard_off;
-                cnt[u] = valid_from(d, r, slot, 8);
-                dst[u] = full + d.full_off + static_cast<int64_t>(r) * d.S + slot;
-                if (cnt[u] == 8) reg[u] = ld<NT>(reinterpret_cast<const u32x4 *>(arena + a));
+    for (int k = 0; k < 8; ++k) {
+        e[k] = 0;
+        if (k < cnt) {
+            const bool in = rr >= static_cast<uint32_t>(r0) && rr < static_cast<uint32_t>(r0 + nr);
+            mine = mine && in;
+            if (in) e[k] = ld_u16(static_cast<const uint16_t *>(base[rr - r0]) + shard_off + ii);
+            if (++ii == S) {
+                ii = 0;
+                ++rr;
             }
         }
+    }
+    if (cnt == 8 && mine) {
+        const u32x4 v = {e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+        st<NT>(reinterpret_cast<u32x4 *>(dst), v);
+        return;
+    }
+    rr = r;
+    ii = i;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (cnt[u] == 8) {
-                st_u128_unaligned<NT>(dst[u], reg[u]);
-            } else if (cnt[u] > 0) {
-                const uint16_t *s = arena + 8 * (q0 + u * TPB);
-                for (int k = 0; k < cnt[u]; ++k) dst[u][k] = s[k];
+    for (int k = 0; k < 8; ++k) {
+        if (k < cnt) {
+            if (rr >= static_cast<uint32_t>(r0) && rr < static_cast<uint32_t>(r0 + nr))
+                st_u16(dst + k, static_cast<uint16_t>(e[k]));
+            if (++ii == S) {
+                ii = 0;
+                ++rr;
             }
         }
     }
 }
 
-template <int TPB, int U, bool NT, bool ATOMIC>
-__global__ __launch_bounds__(TPB) void k_accum_batched(BatchTable tb, RankPtrs accs,
-                                                            const uint16_t *__restrict__ grad, int r0)
+// Generic 64-bit form of one item, for tensors too large for the 32-bit records.
+template <bool NT>
+__device__ __forceinline__ void gather_item_generic(const TensorDesc &d, int64_t a, void *const *base, int r0,
+                                                    int nr, uint16_t *dst)
 {
-    const int r = r0 + static_cast<int>(blockIdx.y);
-    float *__restrict__ arena = static_cast<float *>(accs.p[blockIdx.y]);
-    const int64_t nitem = (tb.arena_elems + 3) >> 2;
-    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
-        u32x2 gv[U];
-        f32x4 av[U];
-        const uint16_t *gp[U];
-        int cnt[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t a = 4 * (q0 + u * TPB);
-            cnt[u] = 0;
-            if (a < tb.arena_elems) {
-                const TensorDesc d = tb.desc[find_tensor(tb, a)];
-                const int64_t slot = a - d.shard_off;
-                cnt[u] = valid_from(d, r, slot, 4);
-                gp[u] = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot;
-                if (cnt[u] == 4) {
-                    gv[u] = ld_u64_unaligned<NT>(gp[u]);
-                    if constexpr (!ATOMIC) av[u] = ld<NT>(reinterpret_cast<const f32x4 *>(arena + a));
-                }
-            }
+    const int64_t j = a - d.full_off;
+    if (j >= d.numel) return;
+    const int cnt = d.numel - j >= 8 ? 8 : static_cast<int>(d.numel - j);
+    int64_t r = ((static_cast<uint64_t>(j) | static_cast<uint64_t>(d.S)) >> 32)
+                    ? j / d.S
+                    : static_cast<int64_t>(static_cast<uint32_t>(j) / static_cast<uint32_t>(d.S));
+    int64_t i = j - r * d.S;
+    if (cnt == 8 && i + 8 <= d.S) {
+        if (r >= r0 && r < r0 + nr)
+            st<NT>(reinterpret_cast<u32x4 *>(dst),
+                   ld_u128_unaligned<NT>(static_cast<const uint16_t *>(base[r - r0]) + d.shard_off + i));
+        return;
+    }
+    for (int k = 0; k < cnt; ++k) {  // at most one such item per shard boundary
+        if (r >= r0 && r < r0 + nr)
+            st_u16(dst + k, ld_u16(static_cast<const uint16_t *>(base[r - r0]) + d.shard_off + i));
+        if (++i == d.S) {
+            i = 0;
+            ++r;
         }
+    }
+}
+
+// First `k` 16-bit elements of a (1 <= k <= 7) followed by the first 8 - k elements of b.
+__device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, int k)
+{
+    const uint64_t alo = a.x | (static_cast<uint64_t>(a.y) << 32), ahi = a.z | (static_cast<uint64_t>(a.w) << 32);
+    const uint64_t blo = b.x | (static_cast<uint64_t>(b.y) << 32), bhi = b.z | (static_cast<uint64_t>(b.w) << 32);
+    const int s = 16 * k;  // bits kept from a
+    uint64_t lo, hi;
+    if (s < 64) {
+        lo = (alo & ((uint64_t{1} << s) - 1)) | (blo << s);
+        hi = (bhi << s) | (blo >> (64 - s));
+    } else if (s == 64) {
+        lo = alo;
+        hi = blo;
+    } else {
+        lo = alo;
+        hi = (ahi & ((uint64_t{1} << (s - 64)) - 1)) | (blo << (s - 64));
+    }
+    u32x4 v;
+    v.x = static_cast<uint32_t>(lo);
+    v.y = static_cast<uint32_t>(lo >> 32);
+    v.z = static_cast<uint32_t>(hi);
+    v.w = static_cast<uint32_t>(hi >> 32);
+    return v;
+}
+
+constexpr int kGatherMaxTensors = kGatherChunks * kMaxTensorsPerChunk + 2;
+
+struct GatherTile {
+    int32_t rel[kGatherMaxTensors];
+    uint32_t S[kGatherMaxTensors];
+    uint32_t numel[kGatherMaxTensors];
+    int64_t shard_off[kGatherMaxTensors];
+    void *base[kRanksPerLaunch];
+};
+
+// Where one 8-element item of the full buffer comes from.
+struct GatherLoc {
+    int64_t shard_off;
+    uint32_t S;       // 0: tensor needs the generic 64-bit path
+    uint32_t r, i;    // owner and slot of the item's first element
+    int cnt;          // valid elements: 0 (gap), 1..8
+    int k;            // staged tensor index within the tile
+};
+
+__device__ __forceinline__ GatherLoc gather_locate(const GatherTile &lds, const GatherRec &one, int n, int a_rel)
+{
+    GatherLoc L;
+    int32_t rel = one.rel;
+    uint32_t numel = one.numel;
+    L.S = one.S;
+    L.shard_off = one.shard_off;
+    L.k = 0;
+    if (n > 1) {
+        int lo = 0, hi = n - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (lds.rel[mid] <= a_rel) lo = mid;
+            else hi = mid - 1;
+        }
+        L.k = lo;
+        rel = lds.rel[lo];
+        L.S = lds.S[lo];
+        numel = lds.numel[lo];
+        L.shard_off = lds.shard_off[lo];
+    }
+    L.r = L.i = 0;
+    L.cnt = 0;
+    if (L.S == 0) return L;
+    const uint32_t j = static_cast<uint32_t>(a_rel - rel);
+    if (j >= numel) return L;  // alignment gap after the tensor
+    L.r = div_owner(j, L.S);
+    L.i = j - L.r * L.S;
+    L.cnt = numel - j >= 8 ? 8 : static_cast<int>(numel - j);
+    return L;
+}
+
+// grid.x = tiles of the full buffer; owners [r0, r0 + nr) are served by this launch.
+// A tile is kGatherChunks chunks; each thread handles its items two at a time: both items'
+// wide loads are issued before either is stored.
+template <bool NT>
+__global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
+                                                                  uint16_t *__restrict__ full, int r0, int nr)
+{
+    constexpr int UG = 2;  // items in flight per thread
+    static_assert(kGatherChunks % UG == 0, "tile must hold a whole number of item groups");
+    __shared__ GatherTile lds;
+    if (threadIdx.x < kRanksPerLaunch) lds.base[threadIdx.x] = arenas.p[threadIdx.x];
+    __syncthreads();
+    const int64_t nchunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t ntiles = (nchunks + kGatherChunks - 1) / kGatherChunks;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();  // LDS reuse across iterations
+        const int64_t c0 = tile * kGatherChunks;
+        const int64_t c1 = c0 + kGatherChunks < nchunks ? c0 + kGatherChunks : nchunks;
+        const int64_t a0 = c0 << kChunkShift;
+        const int t_lo = tb.full_chunk_first[c0];
+        const int n = tb.full_chunk_first[c1] - t_lo + 1;
+        GatherRec one{};
+        if (n == 1) {
+            one = make_gather_rec(tb.desc[t_lo], t_lo, a0);
+        } else {
+            for (int k = threadIdx.x; k < n; k += kBatchThreads) {
+                const GatherRec g = make_gather_rec(tb.desc[t_lo + k], t_lo + k, a0);
+                lds.rel[k] = g.rel;
+                lds.S[k] = g.S;
+                lds.numel[k] = g.numel;
+                lds.shard_off[k] = g.shard_off;
+            }
+            __syncthreads();
+        }
+        const int64_t tile_elems = tb.full_elems - a0;  // elements from the tile start to the buffer end
+
+#pragma unroll 1
+        for (int grp = 0; grp < kGatherChunks / UG; ++grp) {
+            // pass 1: locate the items and issue their wide loads.  An item of a tensor with
+            // S >= 8 lies in one owner's shard or straddles into the next owner's: one or
+            // two wide loads (the first may run past the end of the shard piece into the
+            // owner's next slots, hence `room`).  Everything else -- tensors with S < 8,
+            // owners outside this launch, the very end of an arena, huge tensors -- is
+            // finished element by element in pass 2.
+            u32x4 ra[UG], rb[UG];
+            int kind[UG];   // 0 nothing, 1 wide (spliced with rb if split > 0), 2 the rest
+            int split[UG];  // elements taken from the first owner when the item straddles
+            int cnt[UG];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float *a = arena + 4 * (q0 + u * TPB);
-            if (cnt[u] == 4) {
-                if constexpr (ATOMIC) {
-                    unsafeAtomicAdd(a + 0, widen_lo(gv[u].x));
-                    unsafeAtomicAdd(a + 1, widen_hi(gv[u].x));
-                    unsafeAtomicAdd(a + 2, widen_lo(gv[u].y));
-                    unsafeAtomicAdd(a + 3, widen_hi(gv[u].y));
+            for (int u = 0; u < UG; ++u) {
+                kind[u] = 0;
+                split[u] = 0;
+                cnt[u] = 0;
+                const int a_rel = 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x));
+                if (a_rel >= tile_elems) continue;
+                const GatherLoc L = gather_locate(lds, one, n, a_rel);
+                if (L.S == 0) {
+                    kind[u] = 2;
+                    continue;
+                }
+                if (L.cnt == 0) continue;
+                cnt[u] = L.cnt;
+                const uint32_t rl = L.r - static_cast<uint32_t>(r0);  // huge if r < r0
+                const bool straddles = L.i + static_cast<uint32_t>(L.cnt) > L.S;
+                const bool room = L.shard_off + L.i + 8 <= tb.arena_elems;
+                if (L.S >= 8 && room && rl < static_cast<uint32_t>(nr) &&
+                    (!straddles || rl + 1 < static_cast<uint32_t>(nr))) {
+                    kind[u] = 1;
+                    ra[u] = ld_u128_unaligned<NT>(static_cast<const uint16_t *>(lds.base[rl]) + L.shard_off + L.i);
+                    if (straddles) {
+                        split[u] = static_cast<int>(L.S - L.i);
+                        rb[u] = ld<NT>(reinterpret_cast<const u32x4 *>(
+                            static_cast<const uint16_t *>(lds.base[rl + 1]) + L.shard_off));
+                    }
                 } else {
-                    f32x4 rv = av[u];
-                    rv.x = rv.x + widen_lo(gv[u].x);
-                    rv.y = rv.y + widen_hi(gv[u].x);
-                    rv.z = rv.z + widen_lo(gv[u].y);
-                    rv.w = rv.w + widen_hi(gv[u].y);
-                    st<NT>(reinterpret_cast<f32x4 *>(a), rv);
+                    kind[u] = 2;
                 }
-            } else if (cnt[u] > 0) {
-                for (int k = 0; k < cnt[u]; ++k) add_one<ATOMIC>(a + k, widen_one(gp[u][k]));
+            }
+            // pass 2: aligned wide stores; the rarer kinds are located again and finished
+#pragma unroll
+            for (int u = 0; u < UG; ++u) {
+                const int a_rel = 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x));
+                uint16_t *dst = full + a0 + a_rel;
+                if (kind[u] == 1) {
+                    u32x4 v = ra[u];
+                    if (split[u] > 0) v = splice(ra[u], rb[u], split[u]);
+                    if (cnt[u] == 8) {
+                        st<NT>(reinterpret_cast<u32x4 *>(dst), v);
+                    } else {  // ragged end of the tensor: the slots after it are never written
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 7; ++e)
+                            if (e < cnt[u]) st_u16(dst + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
+                    }
+                } else if (kind[u] == 2) {
+                    const GatherLoc L = gather_locate(lds, one, n, a_rel);
+                    if (L.S == 0) gather_item_generic<NT>(tb.desc[t_lo + L.k], a0 + a_rel, lds.base, r0, nr, dst);
+                    else gather_pieces<NT>(L.r, L.i, L.S, L.shard_off, L.cnt, lds.base, r0, nr, dst);
+                }
             }
         }
     }
 }
 
-template <int TPB, int U, bool NT>
-__global__ __launch_bounds__(TPB) void k_reset_batched(BatchTable tb, RankPtrs accs, int r0)
+// One accumulate item: 4 floats at arena offset a of one owner, in two phases so that a
+// thread can issue the loads of all its items before it consumes any of them.
+struct AccumItem {
+    u32x2 g;
+    f32x4 acc;
+    float *ap;
+    int cnt;  // valid elements: 4 = whole vector, 1..3 = ragged end of a shard, 0 = nothing
+};
+
+template <bool NT, bool ATOMIC>
+__device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc &d, int r, int64_t a,
+                                                float *__restrict__ arena, const uint16_t *__restrict__ grad)
 {
-    const int r = r0 + static_cast<int>(blockIdx.y);
-    float *__restrict__ arena = static_cast<float *>(accs.p[blockIdx.y]);
-    const int64_t nitem = (tb.arena_elems + 3) >> 2;
-    const int64_t ntiles = (nitem + TPB * U - 1) / (TPB * U);
-    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q0 = tile * (TPB * U) + threadIdx.x;
+    const int64_t slot = a - d.shard_off;
+    it.cnt = valid_from(d, r, slot, 4);
+    it.ap = arena + a;
+    if (it.cnt == 0) return;
+    const uint16_t *gp = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot;
+    if (it.cnt == 4) {
+        it.g = ld_u64_unaligned<NT>(gp);
+        if constexpr (!ATOMIC) it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(it.ap));
+    } else {
+        const uint32_t e0 = ld_u16(gp);
+        const uint32_t e1 = it.cnt > 1 ? ld_u16(gp + 1) : 0u;
+        const uint32_t e2 = it.cnt > 2 ? ld_u16(gp + 2) : 0u;
+        it.g.x = e0 | (e1 << 16);
+        it.g.y = e2;
+        if constexpr (!ATOMIC) {
+            it.acc.x = ld_f32(it.ap);
+            it.acc.y = it.cnt > 1 ? ld_f32(it.ap + 1) : 0.0f;
+            it.acc.z = it.cnt > 2 ? ld_f32(it.ap + 2) : 0.0f;
+            it.acc.w = 0.0f;
+        }
+    }
+}
+
+template <bool NT, bool ATOMIC>
+__device__ __forceinline__ void accum_item_store(const AccumItem &it)
+{
+    if (it.cnt == 0) return;
+    if constexpr (ATOMIC) {
+        if (it.cnt == 4) {
+            atomic_add4(it.ap, it.g);
+        } else {
+            unsafeAtomicAdd(it.ap, widen_lo(it.g.x));
+            if (it.cnt > 1) unsafeAtomicAdd(it.ap + 1, widen_hi(it.g.x));
+            if (it.cnt > 2) unsafeAtomicAdd(it.ap + 2, widen_lo(it.g.y));
+        }
+    } else {
+        const f32x4 sum = add4(it.acc, it.g);  // lanes beyond cnt are computed but never stored
+        if (it.cnt == 4) {
+            st<NT>(reinterpret_cast<f32x4 *>(it.ap), sum);
+        } else {
+            st_f32(it.ap, sum.x);
+            if (it.cnt > 1) st_f32(it.ap + 1, sum.y);
+            if (it.cnt > 2) st_f32(it.ap + 2, sum.z);
+        }
+    }
+}
+
+// One-dimensional grid over (tile of the rank arena, group of RG owners), group fastest.
+template <int RG, bool NT, bool ATOMIC>
+__global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, RankPtrs accs,
+                                                                 const uint16_t *__restrict__ grad, int r0, int nr)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int ngroups = (nr + RG - 1) / RG;
+    const int64_t nwork = ntiles * ngroups;
+    for (int64_t w = blockIdx.x; w < nwork; w += gridDim.x) {
+        if (w != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = w / ngroups;
+        const int rl0 = static_cast<int>(w - tile * ngroups) * RG;
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        AccumItem items[kAccumItems][RG];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t a = 4 * (q0 + u * TPB);
-            if (a < tb.arena_elems) {
-                const TensorDesc d = tb.desc[find_tensor(tb, a)];
-                const int cnt = valid_from(d, r, a - d.shard_off, 4);
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = (tile << kChunkShift) + a_rel;
+            const bool live = a < tb.arena_elems;
+            TensorDesc d{};
+            if (live) d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+#pragma unroll
+            for (int k = 0; k < RG; ++k) {
+                const int rl = rl0 + k;
+                items[u][k].cnt = 0;
+                if (live && rl < nr)
+                    accum_item_load<NT, ATOMIC>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u)
+#pragma unroll
+            for (int k = 0; k < RG; ++k) accum_item_store<NT, ATOMIC>(items[u][k]);
+    }
+}
+
+template <int RG, bool NT>
+__global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, RankPtrs accs, int r0, int nr)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int ngroups = (nr + RG - 1) / RG;
+    const int64_t nwork = ntiles * ngroups;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t w = blockIdx.x; w < nwork; w += gridDim.x) {
+        if (w != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = w / ngroups;
+        const int rl0 = static_cast<int>(w - tile * ngroups) * RG;
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = (tile << kChunkShift) + a_rel;
+            if (a >= tb.arena_elems) continue;
+            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+#pragma unroll
+            for (int k = 0; k < RG; ++k) {
+                const int rl = rl0 + k;
+                if (rl >= nr) continue;
+                float *arena = static_cast<float *>(accs.p[rl]);
+                const int cnt = valid_from(d, r0 + rl, a - d.shard_off, 4);
                 if (cnt == 4) st<NT>(reinterpret_cast<f32x4 *>(arena + a), zero);
                 else
-                    for (int k = 0; k < cnt; ++k) arena[a + k] = 0.0f;
+                    for (int e = 0; e < cnt; ++e) st_f32(arena + a + e, 0.0f);
             }
         }
     }

@@ -28,10 +28,12 @@ struct TensorDesc {
 
 // Device-side lookup data of a multi-tensor layout (all pointers are device pointers).
 struct BatchTable {
-    const int64_t *shard_off;    // [T + 1], ascending; shard_off[T] = arena_elems rounded up
-    const TensorDesc *desc;      // [T]
-    const int32_t *chunk_first;  // [n_chunks + 1]: last tensor starting at or before chunk start
+    const TensorDesc *desc;           // [T]
+    const int32_t *chunk_first;       // rank-arena space, [arena tiles + 1]: last tensor whose
+                                      // shard_off is at or before the tile's first element
+    const int32_t *full_chunk_first;  // the same for the full buffer (full_off)
     int64_t arena_elems;
+    int64_t full_elems;
     int32_t T;
 };
 
@@ -42,7 +44,8 @@ struct HostLayout {
     int64_t arena_elems = 0;
     int64_t full_elems = 0;
     int64_t total_numel = 0;
-    std::vector<int32_t> chunk_first;  // built for T > 1
+    std::vector<int32_t> chunk_first;       // built for T > 1
+    std::vector<int32_t> full_chunk_first;  // built for T > 1
 };
 
 // Pure integer layout construction (Section 3.1 even partition, tail padding).
@@ -84,6 +87,7 @@ struct Tuning {
     int nontemporal = 1;       // 1: streaming loads/stores carry the non-temporal hint
     int max_grid_x = 0;        // 0: one workgroup per tile; > 0: cap and loop (persistent style)
     int tile_remap = 0;        // 1: each XCD sweeps its own contiguous eighth of the tiles
+    int batch_rank_group = 0;  // owners per workgroup in batched accumulate/reset: 0 = auto, 1, 2, 4, 8
 };
 Tuning &tuning();
 
@@ -96,6 +100,11 @@ int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64
 int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, void *stream);
 int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr,
                           void *full, void *stream);
+// The batched kernels stage in LDS the tensors that intersect a tile of up to kMaxTileChunks
+// chunks of 2^kChunkShift elements.  With every tensor starting at a multiple of kAlignElems
+// at most one tensor starts per aligned position, so a chunk adds at most
+// 2^kChunkShift / kAlignElems tensors; the host layout checks this bound.
+constexpr int kMaxTensorsPerChunk = (1 << kChunkShift) / static_cast<int>(kAlignElems);
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr,
                          const void *grad, bool atomic, void *stream);
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream);

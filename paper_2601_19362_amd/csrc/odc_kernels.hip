@@ -100,53 +100,76 @@ int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, v
     return finish();
 }
 
-// The batched kernels always use 256-thread workgroups and plain tile order.
-static dim3 batched_grid(int64_t items, int per_block, int nr)
+// The batched kernels use fixed 256-thread workgroups.
+static unsigned batched_grid_x(int64_t work)
 {
-    return dim3(grid_x_for(items, per_block, tuning().max_grid_x), static_cast<unsigned>(nr), 1);
+    return grid_x_for(work, 1, tuning().max_grid_x);
 }
+
+// Owners per workgroup in the batched accumulate / reset kernels: as many as still leave
+// enough workgroups to fill the chip several times over.
+static int rank_group(int64_t tiles, int nr)
+{
+    const int forced = tuning().batch_rank_group;
+    if (forced > 0) return forced;
+    for (int rg = 8; rg > 1; rg >>= 1)
+        if (tiles * ((nr + rg - 1) / rg) >= 4096) return rg;
+    return 1;
+}
+
+#define ODC_DISPATCH_RG(RGV, NTF, CALL)                                            \
+    do {                                                                           \
+        switch (RGV) {                                                             \
+            case 8: { constexpr int RG_ = 8; ODC_DISPATCH_NT(NTF, CALL); } break;   \
+            case 4: { constexpr int RG_ = 4; ODC_DISPATCH_NT(NTF, CALL); } break;   \
+            case 2: { constexpr int RG_ = 2; ODC_DISPATCH_NT(NTF, CALL); } break;   \
+            default: { constexpr int RG_ = 1; ODC_DISPATCH_NT(NTF, CALL); } break;  \
+        }                                                                          \
+    } while (0)
 
 int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr, void *full,
                           void *stream)
 {
-    const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    constexpr int TPB_ = 256;
-    ODC_DISPATCH_U(t.gather_unroll, t.nontemporal != 0,
-                   (k_gather_batched<TPB_, U_, NT_><<<batched_grid((tb.arena_elems + 7) >> 3, TPB_ * U_, nr), TPB_, 0, s>>>(
-                       tb, rp, static_cast<uint16_t *>(full), r0)));
+    const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                    (k_gather_batched<NT_><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
+                        tb, rp, static_cast<uint16_t *>(full), r0, nr)));
     return finish();
 }
 
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *grad,
                          bool atomic, void *stream)
 {
-    const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
-    constexpr int TPB_ = 256;
+    const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int rg = rank_group(tiles, nr);
+    const int64_t work = tiles * ((nr + rg - 1) / rg);
     if (atomic) {
-        ODC_DISPATCH_U(t.accum_unroll, false,
-                       (k_accum_batched<TPB_, U_, NT_, true><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(
-                           tb, rp, g, r0)));
+        ODC_DISPATCH_RG(rg, false,
+                        (k_accum_batched<RG_, NT_, true><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                            tb, rp, g, r0, nr)));
     } else {
-        ODC_DISPATCH_U(t.accum_unroll, t.nontemporal != 0,
-                       (k_accum_batched<TPB_, U_, NT_, false><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(
-                           tb, rp, g, r0)));
+        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+                        (k_accum_batched<RG_, NT_, false><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                            tb, rp, g, r0, nr)));
     }
     return finish();
 }
 
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream)
 {
-    const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    constexpr int TPB_ = 256;
-    ODC_DISPATCH_U(t.reset_unroll, t.nontemporal != 0,
-                   (k_reset_batched<TPB_, U_, NT_><<<batched_grid((tb.arena_elems + 3) >> 2, TPB_ * U_, nr), TPB_, 0, s>>>(tb, rp, r0)));
+    const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int rg = rank_group(tiles, nr);
+    const int64_t work = tiles * ((nr + rg - 1) / rg);
+    ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+                    (k_reset_batched<RG_, NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
     return finish();
 }
 

@@ -62,20 +62,32 @@ int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out)
     L.total_numel = total;
 
     if (T > 1) {
-        // Coarse index for the batched kernels: for every block of 2^kChunkShift arena
-        // elements, the last tensor that starts at or before the block's first element.
+        // Coarse indices for the batched kernels: for every tile of 2^kChunkShift elements of
+        // the rank-arena space (and of the full-buffer space), the last tensor that starts at
+        // or before the tile's first element.
         const int64_t chunk = int64_t{1} << kChunkShift;
-        const int64_t n_chunks = (L.arena_elems + chunk - 1) / chunk;
-        try {
-            L.chunk_first.resize(static_cast<size_t>(n_chunks) + 1);
-        } catch (...) {
-            return ODC_ERR_NOMEM;
-        }
-        int t = 0;
-        for (int64_t c = 0; c <= n_chunks; ++c) {
-            const int64_t start = c * chunk;
-            while (t + 1 < T && L.desc[static_cast<size_t>(t) + 1].shard_off <= start) ++t;
-            L.chunk_first[static_cast<size_t>(c)] = t;
+        for (int space = 0; space < 2; ++space) {
+            const int64_t extent = space == 0 ? L.arena_elems : L.full_elems;
+            std::vector<int32_t> &index = space == 0 ? L.chunk_first : L.full_chunk_first;
+            const int64_t n_chunks = (extent + chunk - 1) / chunk;
+            try {
+                index.resize(static_cast<size_t>(n_chunks) + 1);
+            } catch (...) {
+                return ODC_ERR_NOMEM;
+            }
+            int t = 0;
+            for (int64_t c = 0; c <= n_chunks; ++c) {
+                const int64_t start = c * chunk;
+                while (t + 1 < T) {
+                    const TensorDesc &next = L.desc[static_cast<size_t>(t) + 1];
+                    if ((space == 0 ? next.shard_off : next.full_off) > start) break;
+                    ++t;
+                }
+                index[static_cast<size_t>(c)] = t;
+                // the kernels size their LDS staging area from this bound
+                if (c > 0 && t - index[static_cast<size_t>(c) - 1] > kMaxTensorsPerChunk)
+                    return ODC_ERR_OVERFLOW;
+            }
         }
     }
     *out = std::move(L);

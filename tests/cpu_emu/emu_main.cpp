@@ -5,7 +5,7 @@
 // rank buffer is its own exactly-sized heap block, so any access outside the valid range of
 // a buffer is reported.  The test compares the outputs with the CPU oracle.
 //
-// usage: emu <dir> <op> <R> <threads> <unroll> <nt> <remap> <atomic> <grid_cap>
+// usage: emu <dir> <op> <R> <threads> <unroll> <nt> <remap> <atomic> <grid_cap> <rank_group>
 //   dir holds numel.i64 [T]; arenas.u16 [R*arena] (gather); full.u16 [full] (gather in/out);
 //   grad.u16 [full] and acc.f32 [R*arena] (accum / reset, in/out)
 #include "hip_shim.h"
@@ -13,6 +13,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/odc.h"
@@ -61,6 +62,33 @@ void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
             }
 }
 
+// Workgroups one after the other, each on `tpb` host threads that meet at the barrier
+// behind __syncthreads().  `kernel` is called once per (thread, workgroup).
+template <typename F>
+void run_grid_threaded(unsigned tpb, unsigned gx, F &&kernel)
+{
+    gridDim.x = gx;
+    gridDim.y = 1;
+    blockDim.x = tpb;
+    pthread_barrier_t barrier;
+    pthread_barrier_init(&barrier, nullptr, tpb);
+    emu_block_barrier = &barrier;
+    std::vector<std::thread> pool;
+    for (unsigned t = 0; t < tpb; ++t)
+        pool.emplace_back([&, t] {
+            for (unsigned x = 0; x < gx; ++x) {
+                blockIdx.x = x;
+                blockIdx.y = 0;
+                threadIdx.x = t;
+                kernel();
+                pthread_barrier_wait(&barrier);  // the shared LDS image is reused by the next workgroup
+            }
+        });
+    for (auto &th : pool) th.join();
+    emu_block_barrier = nullptr;
+    pthread_barrier_destroy(&barrier);
+}
+
 #define EMU_NT(NTF, CALL)                             \
     do {                                              \
         if (NTF) { constexpr bool NT_ = true; CALL; } \
@@ -85,6 +113,16 @@ void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
         }                                                                         \
     } while (0)
 
+#define EMU_RG(RGV, NTF, CALL)                                            \
+    do {                                                                  \
+        switch (RGV) {                                                    \
+            case 8: { constexpr int RG_ = 8; EMU_NT(NTF, CALL); } break;   \
+            case 4: { constexpr int RG_ = 4; EMU_NT(NTF, CALL); } break;   \
+            case 2: { constexpr int RG_ = 2; EMU_NT(NTF, CALL); } break;   \
+            default: { constexpr int RG_ = 1; EMU_NT(NTF, CALL); } break;  \
+        }                                                                 \
+    } while (0)
+
 // x extent as the launcher computes it
 unsigned gx_for(int64_t items, int per_block, int cap, int remap)
 {
@@ -97,14 +135,14 @@ unsigned gx_for(int64_t items, int per_block, int cap, int remap)
 
 int main(int argc, char **argv)
 {
-    if (argc != 10) {
-        std::fprintf(stderr, "usage: emu dir op R threads unroll nt remap atomic grid_cap\n");
+    if (argc != 11) {
+        std::fprintf(stderr, "usage: emu dir op R threads unroll nt remap atomic grid_cap rank_group\n");
         return 2;
     }
     const std::string dir = argv[1], op = argv[2];
     const int R = std::atoi(argv[3]), threads = std::atoi(argv[4]), unroll = std::atoi(argv[5]);
     const int nt = std::atoi(argv[6]), remap = std::atoi(argv[7]), atomic = std::atoi(argv[8]);
-    const int cap = std::atoi(argv[9]);
+    const int cap = std::atoi(argv[9]), rg = std::atoi(argv[10]);
     using namespace odc;
 
     std::vector<int64_t> numel = read_file<int64_t>(dir + "/numel.i64");
@@ -115,9 +153,7 @@ int main(int argc, char **argv)
         return 3;
     }
     const size_t arena = static_cast<size_t>(H.arena_elems), full_n = static_cast<size_t>(H.full_elems);
-    std::vector<int64_t> offs(static_cast<size_t>(H.T));
-    for (int t = 0; t < H.T; ++t) offs[static_cast<size_t>(t)] = H.desc[static_cast<size_t>(t)].shard_off;
-    BatchTable tb{offs.data(), H.desc.data(), H.chunk_first.data(), H.arena_elems, H.T};
+    BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.arena_elems, H.full_elems, H.T};
     const bool flat = H.T == 1;
     const int64_t S = H.desc[0].S, N = H.desc[0].numel;
 
@@ -144,10 +180,10 @@ int main(int argc, char **argv)
                                  k_gather_flat<TPB_, U_, NT_>(rp, full, S, N, r0, remap);
                              }));
             } else {
-                constexpr int TPB_ = 256;
-                EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 7) >> 3, TPB_ * U_, cap, 0), nr, [&] {
-                          k_gather_batched<TPB_, U_, NT_>(tb, rp, full, r0);
-                      }));
+                const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
+                const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
+                EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap),
+                                             [&] { k_gather_batched<NT_>(tb, rp, full, r0, nr); }));
             }
         }
         write_file(dir + "/full.out", full, full_n);
@@ -181,9 +217,9 @@ int main(int argc, char **argv)
                                  run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr,
                                           [&] { k_reset_flat<TPB_, U_, NT_>(rp, S, N, r0, remap); }));
                 } else {
-                    constexpr int TPB_ = 256;
-                    EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr,
-                                               [&] { k_reset_batched<TPB_, U_, NT_>(tb, rp, r0); }));
+                    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap),
+                                                     [&] { k_reset_batched<RG_, NT_>(tb, rp, r0, nr); }));
                 }
             } else if (flat) {
                 if (atomic) {
@@ -198,15 +234,15 @@ int main(int argc, char **argv)
                                  }));
                 }
             } else {
-                constexpr int TPB_ = 256;
+                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
                 if (atomic) {
-                    EMU_U(unroll, 0, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr, [&] {
-                              k_accum_batched<TPB_, U_, NT_, true>(tb, rp, grad, r0);
-                          }));
+                    EMU_RG(rg, 0, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                               k_accum_batched<RG_, NT_, true>(tb, rp, grad, r0, nr);
+                           }));
                 } else {
-                    EMU_U(unroll, nt, run_grid(TPB_, gx_for((tb.arena_elems + 3) >> 2, TPB_ * U_, cap, 0), nr, [&] {
-                              k_accum_batched<TPB_, U_, NT_, false>(tb, rp, grad, r0);
-                          }));
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                               k_accum_batched<RG_, NT_, false>(tb, rp, grad, r0, nr);
+                           }));
                 }
             }
         }

@@ -26,7 +26,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(CLANG), reason="ROCm clang++ 
 def emu(tmp_path_factory):
     exe = str(tmp_path_factory.mktemp("emu") / "emu")
     subprocess.run([CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
-                    "-fno-sanitize-recover=all", "-ffp-contract=off",
+                    "-fno-sanitize-recover=all", "-ffp-contract=off", "-pthread",
                     os.path.join(ROOT, "tests", "cpu_emu", "emu_main.cpp"),
                     os.path.join(ROOT, "paper_2601_19362_amd", "csrc", "odc_layout.cpp"),
                     "-o", exe], check=True)
@@ -45,9 +45,9 @@ def placement(numel, R):
     return S, so, fo, so[-1] + S[-1], fo[-1] + numel[-1]
 
 
-def run(emu, d, op, R, threads=256, unroll=4, nt=1, remap=0, atomic=0, cap=0):
+def run(emu, d, op, R, threads=256, unroll=4, nt=1, remap=0, atomic=0, cap=0, rg=1):
     p = subprocess.run([emu, str(d), op, str(R), str(threads), str(unroll), str(nt), str(remap),
-                        str(atomic), str(cap)], capture_output=True, text=True,
+                        str(atomic), str(cap), str(rg)], capture_output=True, text=True,
                        env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0"})
     assert p.returncode == 0, p.stderr[-3000:]
 
@@ -72,6 +72,10 @@ CASES = [
     ([3, 1, 1, 2, 70, 5000, 2, 2, 129, 1], 64),
     ([30000, 17, 2048, 2049], 5),
     ([5] * 70, 70),                   # more than 64 ranks: two launch groups
+    ([1] * 600 + [9000] + [3] * 50, 4),   # tiles packed with the maximum number of tensors
+    ([2047, 2049, 1, 4096, 8, 16384 + 7, 5], 3),  # tensors ending at, before and after tile edges
+    ([129] * 40 + [70000], 66),       # batched with more than 64 ranks
+    ([1] * 1100 + [20000, 2], 2),     # a gather tile whose LDS index is filled to the brim
 ]
 
 
@@ -93,15 +97,15 @@ def test_emulated_gather(oracle, emu, tmp_path, numel, R, threads, unroll, nt, r
 
 
 @pytest.mark.parametrize("numel,R", CASES)
-@pytest.mark.parametrize("threads,unroll,nt,remap,atomic,cap", [(256, 4, 1, 0, 0, 0), (64, 1, 1, 0, 0, 0),
-                                                                (128, 2, 0, 1, 0, 0), (64, 4, 1, 0, 1, 2),
-                                                                (64, 1, 1, 1, 0, 0)])
-def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, threads, unroll, nt, remap, atomic, cap):
+@pytest.mark.parametrize("threads,unroll,nt,remap,atomic,cap,rg", [
+    (256, 4, 1, 0, 0, 0, 1), (64, 1, 1, 0, 0, 0, 8), (128, 2, 0, 1, 0, 0, 4), (64, 4, 1, 0, 1, 2, 2),
+    (64, 1, 1, 1, 0, 0, 8)])
+def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, threads, unroll, nt, remap, atomic, cap, rg):
     S, so, fo, arena, full_n = placement(numel, R)
     np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
     acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
     np.concatenate(acc).tofile(tmp_path / "acc.f32")
-    run(emu, tmp_path, "reset", R, threads=threads, unroll=unroll, nt=nt, remap=remap, cap=cap)
+    run(emu, tmp_path, "reset", R, threads=threads, unroll=unroll, nt=nt, remap=remap, cap=cap, rg=rg)
     got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
     oracle.reset_batched(acc, numel, so)
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
@@ -109,7 +113,8 @@ def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, threads,
         g = inputs.normal_bf16(full_n, 1e-2, seed=(2, k))
         g.tofile(tmp_path / "grad.u16")
         got.tofile(tmp_path / "acc.f32")
-        run(emu, tmp_path, "accum", R, threads=threads, unroll=unroll, nt=nt, remap=remap, atomic=atomic, cap=cap)
+        run(emu, tmp_path, "accum", R, threads=threads, unroll=unroll, nt=nt, remap=remap, atomic=atomic, cap=cap,
+            rg=rg)
         got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
         oracle.accumulate_batched(g, acc, numel, so, fo)
         assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
