@@ -30,6 +30,7 @@ _SRC = os.path.join(_HERE, "odc_oracle.c")
 _BUILD_DIR = os.path.join(_HERE, "_build")
 _LIB_PATH = os.path.join(_BUILD_DIR, "libodc_oracle.so")
 _CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-shared", "-fPIC"]
+_LDLIBS = ["-lm"]
 
 _lib = None
 _lock = threading.Lock()
@@ -46,7 +47,7 @@ def build(force: bool = False) -> str:
              or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC))
     if force or stale:
         tmp = _LIB_PATH + f".tmp{os.getpid()}"
-        subprocess.run(["gcc", *_CFLAGS, _SRC, "-o", tmp], check=True)
+        subprocess.run(["gcc", *_CFLAGS, _SRC, "-o", tmp, *_LDLIBS], check=True)
         os.replace(tmp, _LIB_PATH)
     return _LIB_PATH
 
@@ -74,6 +75,17 @@ def _load():
             lib.odc_oracle_reset_batched.argtypes = [_vpp, _i64, _vp, _vp, _i64]
             lib.odc_oracle_accumulate_batched.restype = ctypes.c_int
             lib.odc_oracle_accumulate_batched.argtypes = [_vp, _vpp, _i64, _vp, _vp, _vp, _i64]
+            _f32 = ctypes.c_float
+            lib.odc_oracle_accumulate_weighted.restype = None
+            lib.odc_oracle_accumulate_weighted.argtypes = [_vp, _vpp, _i64, _i64, _f32, _i64, _i64]
+            lib.odc_oracle_retrieve_f32.restype = None
+            lib.odc_oracle_retrieve_f32.argtypes = [_vpp, _vpp, _i64, _i64, _f32, _i64, _i64]
+            lib.odc_oracle_retrieve_bf16.restype = None
+            lib.odc_oracle_retrieve_bf16.argtypes = [_vpp, _vpp, _i64, _i64, _f32, _i64, _i64]
+            lib.odc_oracle_accumulate_weighted_batched.restype = ctypes.c_int
+            lib.odc_oracle_accumulate_weighted_batched.argtypes = [_vp, _vpp, _i64, _vp, _vp, _vp, _i64, _f32]
+            lib.odc_oracle_retrieve_batched.restype = ctypes.c_int
+            lib.odc_oracle_retrieve_batched.argtypes = [_vpp, _vpp, _i64, _vp, _vp, _i64, _f32, ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -105,8 +117,20 @@ def _split(N: int, nthreads: int):
     return [(edges[k], edges[k + 1]) for k in range(nthreads) if edges[k + 1] > edges[k]]
 
 
-def _run_ranges(fn, N: int, nthreads: int) -> None:
-    """Call fn(j_begin, j_end) over a partition of [0, N); ctypes drops the GIL."""
+def _run_ranges(fn, N: int, nthreads: int, ranges=None) -> None:
+    """Call fn(j_begin, j_end) over a partition of [0, N) (or over the given flat-index
+    ranges only, for sampled checks of very large tensors); ctypes drops the GIL."""
+    if ranges is not None:
+        end = 0
+        for a, b in sorted(ranges):
+            if not 0 <= a <= b <= N:
+                raise ValueError(f"range ({a}, {b}) outside [0, {N}]")
+            if a < end:
+                raise ValueError("ranges overlap: an element would be processed twice")
+            end = b
+        for a, b in ranges:
+            fn(a, b)
+        return
     ranges = _split(N, nthreads)
     if len(ranges) <= 1:
         fn(0, N)
@@ -150,8 +174,9 @@ def make_shards(flat: np.ndarray, R: int, pad_bits: int = 0xDEAD) -> list:
 
 
 # ----------------------------------------------------------------------------- primitives
-def gather(shards, N: int, full: np.ndarray, nthreads: int = 1) -> np.ndarray:
-    """full[r*S + i] = shard_r[i] for valid i; full[N:] is left untouched.  Returns full."""
+def gather(shards, N: int, full: np.ndarray, nthreads: int = 1, ranges=None) -> np.ndarray:
+    """full[r*S + i] = shard_r[i] for valid i; full[N:] is left untouched.  Returns full.
+    With `ranges` only the flat indices inside those [a, b) intervals are produced."""
     R = len(shards)
     S = shard_elems(N, R)
     for r, sh in enumerate(shards):
@@ -159,11 +184,11 @@ def gather(shards, N: int, full: np.ndarray, nthreads: int = 1) -> np.ndarray:
     _check(full, np.uint16, N, "full")
     lib = _load()
     ptrs = _ptr_array(shards)
-    _run_ranges(lambda a, b: lib.odc_oracle_gather(ptrs, N, R, full.ctypes.data, a, b), N, nthreads)
+    _run_ranges(lambda a, b: lib.odc_oracle_gather(ptrs, N, R, full.ctypes.data, a, b), N, nthreads, ranges)
     return full
 
 
-def reset(acc, N: int, nthreads: int = 1) -> None:
+def reset(acc, N: int, nthreads: int = 1, ranges=None) -> None:
     """Valid accumulator elements become +0.0f; padding slots keep their content."""
     R = len(acc)
     S = shard_elems(N, R)
@@ -171,10 +196,10 @@ def reset(acc, N: int, nthreads: int = 1) -> None:
         _check(a, np.float32, S, f"acc[{r}]")
     lib = _load()
     ptrs = _ptr_array(acc)
-    _run_ranges(lambda a, b: lib.odc_oracle_reset(ptrs, N, R, a, b), N, nthreads)
+    _run_ranges(lambda a, b: lib.odc_oracle_reset(ptrs, N, R, a, b), N, nthreads, ranges)
 
 
-def accumulate(g: np.ndarray, acc, N: int, nthreads: int = 1) -> None:
+def accumulate(g: np.ndarray, acc, N: int, nthreads: int = 1, ranges=None) -> None:
     """Apply ONE contribution: acc_r[i] = fl32(acc_r[i] + widen(g[r*S+i])) for valid i."""
     R = len(acc)
     S = shard_elems(N, R)
@@ -183,7 +208,38 @@ def accumulate(g: np.ndarray, acc, N: int, nthreads: int = 1) -> None:
         _check(a, np.float32, S, f"acc[{r}]")
     lib = _load()
     ptrs = _ptr_array(acc)
-    _run_ranges(lambda a, b: lib.odc_oracle_accumulate(g.ctypes.data, ptrs, N, R, a, b), N, nthreads)
+    _run_ranges(lambda a, b: lib.odc_oracle_accumulate(g.ctypes.data, ptrs, N, R, a, b), N, nthreads, ranges)
+
+
+def accumulate_weighted(g: np.ndarray, acc, N: int, weight: float, nthreads: int = 1, ranges=None) -> None:
+    """ONE weighted contribution: acc_r[i] = fma32(weight, widen(g[r*S+i]), acc_r[i]) (Section 2.1,
+    w_m != 1; one rounding per element)."""
+    R = len(acc)
+    S = shard_elems(N, R)
+    _check(g, np.uint16, N, "g")
+    for r, a in enumerate(acc):
+        _check(a, np.float32, S, f"acc[{r}]")
+    lib = _load()
+    ptrs = _ptr_array(acc)
+    w = float(np.float32(weight))
+    _run_ranges(lambda a, b: lib.odc_oracle_accumulate_weighted(g.ctypes.data, ptrs, N, R, w, a, b),
+                N, nthreads, ranges)
+
+
+def retrieve(acc, out, N: int, scale: float = 1.0, nthreads: int = 1, ranges=None) -> None:
+    """Minibatch-end retrieval (Section 3.2): out_r[i] = cast(fl32(scale * acc_r[i])) for valid i.
+    `out` arrays are float32 (no further rounding) or uint16 (bf16 bits, round-to-nearest-even)."""
+    R = len(acc)
+    S = shard_elems(N, R)
+    to_bf16 = out[0].dtype == np.uint16
+    for r in range(R):
+        _check(acc[r], np.float32, S, f"acc[{r}]")
+        _check(out[r], np.uint16 if to_bf16 else np.float32, S, f"out[{r}]")
+    lib = _load()
+    pa, po = _ptr_array(acc), _ptr_array(out)
+    sc = float(np.float32(scale))
+    fn = lib.odc_oracle_retrieve_bf16 if to_bf16 else lib.odc_oracle_retrieve_f32
+    _run_ranges(lambda a, b: fn(pa, po, N, R, sc, a, b), N, nthreads, ranges)
 
 
 def scatter_accumulate_ordered(grads, acc, N: int, nthreads: int = 1) -> int:
@@ -273,3 +329,28 @@ def _bounds_batched(arenas, dtype, numel, shard_off, R, what) -> None:
     need = int((shard_off + S).max())
     for r, a in enumerate(arenas):
         _check(a, dtype, need, f"{what}[{r}]")
+
+
+def accumulate_weighted_batched(g_full: np.ndarray, acc_arenas, numel, shard_off, full_off, weight: float) -> None:
+    R = len(acc_arenas)
+    numel, shard_off, full_off = _i64_array(numel), _i64_array(shard_off), _i64_array(full_off)
+    _bounds_batched(acc_arenas, np.float32, numel, shard_off, R, "acc_arenas")
+    _check(g_full, np.uint16, int((full_off + numel).max()), "g_full")
+    rc = _load().odc_oracle_accumulate_weighted_batched(
+        g_full.ctypes.data, _ptr_array(acc_arenas), numel.shape[0], numel.ctypes.data,
+        shard_off.ctypes.data, full_off.ctypes.data, R, float(np.float32(weight)))
+    if rc != 0:
+        raise MemoryError("oracle scratch allocation failed")
+
+
+def retrieve_batched(acc_arenas, out_arenas, numel, shard_off, scale: float = 1.0) -> None:
+    R = len(acc_arenas)
+    numel, shard_off = _i64_array(numel), _i64_array(shard_off)
+    to_bf16 = out_arenas[0].dtype == np.uint16
+    _bounds_batched(acc_arenas, np.float32, numel, shard_off, R, "acc_arenas")
+    _bounds_batched(out_arenas, np.uint16 if to_bf16 else np.float32, numel, shard_off, R, "out_arenas")
+    rc = _load().odc_oracle_retrieve_batched(_ptr_array(acc_arenas), _ptr_array(out_arenas), numel.shape[0],
+                                             numel.ctypes.data, shard_off.ctypes.data, R,
+                                             float(np.float32(scale)), 1 if to_bf16 else 0)
+    if rc != 0:
+        raise MemoryError("oracle scratch allocation failed")

@@ -17,8 +17,8 @@
  *     accumulates each contribution when it is received.
  *   - Section 2.1: the accumulated gradient is the sum over microbatches of
  *     w_m * g^(m); here w_m = 1.
- *   - Section 3.2: accumulated gradients are retrieved at the minibatch end,
- *     so the accumulators are cleared before the next minibatch (reset).
+ *   - Section 3.2: accumulated gradients are retrieved at the minibatch end
+ *     (retrieve), so the accumulators are cleared before the next minibatch (reset).
  *
  * Readings where the paper is silent (kept identical in the design notes):
  *   - element types: bf16 parameters and gradient contributions (raw 16-bit
@@ -36,6 +36,7 @@
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC.  No flush-to-
  * zero: x86-64 SSE default keeps subnormals.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -148,6 +149,75 @@ void odc_oracle_accumulate(const uint16_t *g, float *const *acc, int64_t N, int6
 }
 
 /*
+ * Weighted contribution (Section 2.1: the accumulated gradient is the sum over microbatches
+ * of w_m * g^(m), with w_m = 1 for a plain sum "or proportional weighting when averaging by
+ * tokens or samples").  The paper does not say how the product is rounded; the reading taken
+ * is one fused multiply-add in binary32 per element,
+ *   acc_r[i] = fma32(w, widen(g[r*S + i]), acc_r[i]),
+ * i.e. a single rounding of the exact value w*g + acc.  fmaf() is the correctly rounded C99
+ * routine.  With w = 1 this is the unweighted contribution bit for bit.
+ */
+void odc_oracle_accumulate_weighted(const uint16_t *g, float *const *acc, int64_t N, int64_t R,
+                                    float w, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i)
+            acc[r][i] = fmaf(w, widen_bf16(g[r * S + i]), acc[r][i]);
+    }
+}
+
+/* binary32 -> bf16, round-to-nearest-even; a NaN stays a (quiet) NaN. */
+static uint16_t narrow_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/*
+ * Retrieval at the minibatch end (Section 3.2: integrating ODC needs only "retrieving
+ * accumulated gradients at the minibatch end"; after it each owner holds what reduce-scatter
+ * would have left on the device, Section 2.2).  Owner r's valid accumulator elements are
+ * read, multiplied by `scale` (1 for a plain sum, 1/tokens or 1/samples for an average) with
+ * one binary32 multiplication, and written out either as binary32 or, rounded once more to
+ * nearest-even, as bf16.  The accumulators are not changed; padding slots of the outputs are
+ * never written.
+ */
+void odc_oracle_retrieve_f32(const float *const *acc, float *const *out, int64_t N, int64_t R,
+                             float scale, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i)
+            out[r][i] = scale * acc[r][i];
+    }
+}
+
+void odc_oracle_retrieve_bf16(const float *const *acc, uint16_t *const *out, int64_t N, int64_t R,
+                              float scale, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i) {
+            float v = scale * acc[r][i];
+            out[r][i] = narrow_to_bf16(v);
+        }
+    }
+}
+
+/*
  * Batched forms (the many-small-tensor workload): T flat parameters, each
  * partitioned on its own by the rule above.  Where tensor t sits inside an
  * owner's buffer (shard_off[t], in elements, the same for every owner) and
@@ -194,5 +264,47 @@ int odc_oracle_accumulate_batched(const uint16_t *g_full, float *const *acc_aren
         odc_oracle_accumulate(g_full + full_off[t], ac, numel[t], R, 0, numel[t]);
     }
     free(ac);
+    return 0;
+}
+
+int odc_oracle_accumulate_weighted_batched(const uint16_t *g_full, float *const *acc_arenas, int64_t T,
+                                           const int64_t *numel, const int64_t *shard_off,
+                                           const int64_t *full_off, int64_t R, float w)
+{
+    float **ac = (float **)malloc((size_t)R * sizeof *ac);
+    if (!ac) return -1;
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < R; ++r) ac[r] = acc_arenas[r] + shard_off[t];
+        odc_oracle_accumulate_weighted(g_full + full_off[t], ac, numel[t], R, w, 0, numel[t]);
+    }
+    free(ac);
+    return 0;
+}
+
+/* out_is_bf16 = 0: out arenas hold binary32; 1: bf16 bit patterns. */
+int odc_oracle_retrieve_batched(const float *const *acc_arenas, void *const *out_arenas, int64_t T,
+                                const int64_t *numel, const int64_t *shard_off, int64_t R,
+                                float scale, int out_is_bf16)
+{
+    const float **ac = (const float **)malloc((size_t)R * sizeof *ac);
+    void **ou = (void **)malloc((size_t)R * sizeof *ou);
+    if (!ac || !ou) {
+        free(ac);
+        free(ou);
+        return -1;
+    }
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < R; ++r) {
+            ac[r] = acc_arenas[r] + shard_off[t];
+            ou[r] = out_is_bf16 ? (void *)((uint16_t *)out_arenas[r] + shard_off[t])
+                                : (void *)((float *)out_arenas[r] + shard_off[t]);
+        }
+        if (out_is_bf16)
+            odc_oracle_retrieve_bf16(ac, (uint16_t *const *)ou, numel[t], R, scale, 0, numel[t]);
+        else
+            odc_oracle_retrieve_f32(ac, (float *const *)ou, numel[t], R, scale, 0, numel[t]);
+    }
+    free(ac);
+    free(ou);
     return 0;
 }

@@ -81,3 +81,74 @@ def test_7b_layer(oracle):
 def test_32b_layer(oracle):
     w = inputs.workload("32b")
     full_layer_case(oracle, w.numel[0], w.R, [(0, 0), (31, 3)], seed=w.seed)
+
+
+def test_32b_rotating_window(oracle):
+    """The 32B-shaped workload keeps only 4 layers' buffers resident and reuses buffer set
+    l mod 4 for layer l.  Eight layers go through the four sets (each set is reused once, so
+    stale contents from its previous layer would show); every layer is gathered and receives
+    three contributions.  Checked against the oracle on sampled flat-index windows of every
+    layer -- the start and end of the tensor, every shard boundary and windows in between --
+    which the oracle computes one by one."""
+    w = inputs.workload("32b")
+    N, R = w.numel[0], w.R
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    nset = w.resident_layers
+    sets = [([torch.empty(S, dtype=torch.bfloat16, device=dev) for _ in range(R)],
+             [torch.empty(S, dtype=torch.float32, device=dev) for _ in range(R)]) for _ in range(nset)]
+    full = torch.empty(N, dtype=torch.bfloat16, device=dev)
+    win = 2048
+    ranges = [(0, win), (N - win, N)]
+    for r in range(1, R):
+        ranges.append((r * S - win // 2, r * S + win // 2))
+    rng = np.random.default_rng(7)
+    for r in rng.integers(0, R, size=16):   # windows strictly inside a shard, away from its edges
+        a = int(r) * S + int(rng.integers(2 * win, S - 3 * win))
+        if all(b <= a or a + win <= x for x, b in ranges):
+            ranges.append((a, a + win))
+    contribs = [(0, 0), (5, 1), (31, 0)]
+    for layer in range(2 * nset):
+        print(f"32b window: layer {layer} -> buffer set {layer % nset}", flush=True)
+        params, acc = sets[layer % nset]
+        flat = inputs.device_uniform_bf16(N, -0.05, 0.05, 100 + layer, dev)
+        for r in range(R):
+            params[r].copy_(flat[r * S:(r + 1) * S])
+        L.gather(params, full)
+        L.reset_accum(acc)
+        grads = []
+        for k, (wk, m) in enumerate(contribs):
+            g = inputs.device_normal_bf16(N, 1e-3, 1000 * layer + k, dev)
+            L.scatter_accumulate(g, acc, wk, m)
+            grads.append(g)
+        torch.cuda.synchronize()
+        # host side: only the sampled windows are copied and computed
+        flat_h = np.zeros(N, dtype=np.uint16)
+        full_h = np.zeros(N, dtype=np.uint16)
+        shards_h = [np.zeros(S, dtype=np.uint16) for _ in range(R)]
+        acc_h = [np.full(S, 123.0, dtype=np.float32) for _ in range(R)]
+        grads_h = [np.zeros(N, dtype=np.uint16) for _ in contribs]
+        for a, b in ranges:
+            flat_h[a:b] = flat[a:b].view(torch.int16).cpu().numpy().view(np.uint16)
+            for gh, g in zip(grads_h, grads):
+                gh[a:b] = g[a:b].view(torch.int16).cpu().numpy().view(np.uint16)
+            for r in range(R):
+                lo, hi = max(a, r * S), min(b, (r + 1) * S)
+                if hi > lo:
+                    shards_h[r][lo - r * S:hi - r * S] = params[r][lo - r * S:hi - r * S].view(torch.int16).cpu().numpy().view(np.uint16)
+        oracle.gather(shards_h, N, full_h, ranges=ranges)
+        oracle.reset(acc_h, N, ranges=ranges)
+        for gh in grads_h:
+            oracle.accumulate(gh, acc_h, N, ranges=ranges)
+        for a, b in ranges:
+            got = full[a:b].view(torch.int16).cpu().numpy().view(np.uint16)
+            assert_bits_equal(got, full_h[a:b], f"layer {layer} gather [{a},{b})")
+            assert np.array_equal(got, flat_h[a:b])
+            for r in range(R):
+                lo, hi = max(a, r * S), min(b, (r + 1) * S)
+                if hi > lo:
+                    assert_bits_equal(acc[r][lo - r * S:hi - r * S].cpu().numpy(), acc_h[r][lo - r * S:hi - r * S],
+                                      f"layer {layer} accumulate rank {r} [{lo},{hi})")
+        del flat, grads
+    L.close()

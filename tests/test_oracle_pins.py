@@ -328,6 +328,35 @@ def test_element_range_threads_do_not_change_bits(oracle):
         assert np.array_equal(bits32(x), bits32(y))
 
 
+def test_sampled_ranges_touch_only_their_elements(oracle):
+    """The flat-index range arguments (used for sampled checks at the largest shapes): inside
+    the ranges the result equals the full computation, outside nothing is touched."""
+    N, R = 10_007, 4
+    S = -(-N // R)
+    ranges = [(0, 5), (1200, 1210), (S - 3, S + 4), (N - 2, N)]
+    inside = np.zeros(N, dtype=bool)
+    for a, b in ranges:
+        inside[a:b] = True
+    flat = inputs.uniform_bf16(N, -1, 1, seed=51)
+    shards = oracle.make_shards(flat, R)
+    full = np.full(N, 0xBEEF, dtype=np.uint16)
+    oracle.gather(shards, N, full, ranges=ranges)
+    assert np.array_equal(full[inside], flat[inside]) and (full[~inside] == 0xBEEF).all()
+    g = inputs.normal_bf16(N, 1e-3, seed=52)
+    a_full, a_part = new_acc(S, R), new_acc(S, R)
+    oracle.reset(a_full, N)
+    oracle.accumulate(g, a_full, N)
+    oracle.reset(a_part, N, ranges=ranges)
+    oracle.accumulate(g, a_part, N, ranges=ranges)
+    f, p = np.concatenate(a_full)[:N], np.concatenate(a_part)[:N]
+    assert np.array_equal(bits32(f[inside]), bits32(p[inside]))
+    assert (p[~inside] == PAD32).all()
+    with pytest.raises(ValueError):
+        oracle.gather(shards, N, full, ranges=[(5, N + 1)])
+    with pytest.raises(ValueError):
+        oracle.accumulate(g, a_part, N, ranges=[(0, 10), (9, 20)])
+
+
 def test_batched_equals_per_tensor_numpy(oracle):
     """Batched forms against numpy slicing done here: tensor t of owner r sits at
     arena_r[off_t : off_t + S_t]; gaps between tensors and padding keep their sentinels."""
