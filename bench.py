@@ -253,6 +253,13 @@ def main():
     acc_med, acc_min = time_kernel(lambda: _accum_once(L, pool[0], s0[1], odc), torch)
     gat_med, gat_min = time_kernel(lambda: L.gather(s0[0], full), torch)
     rst_med, rst_min = time_kernel(lambda: L.reset_accum(s0[1]), torch)
+    wac_med, wac_min = time_kernel(lambda: _accum_once(L, pool[1], s0[1], odc, weight=0.37), torch)
+    arena = L.rank_arena_elems()
+    out32 = [torch.empty(arena, dtype=torch.float32, device="cuda") for _ in range(w.R)]
+    r32_med, r32_min = time_kernel(lambda: L.retrieve_grads(s0[1], out32, 0.125, odc.ODC_OUT_F32), torch)
+    out16 = [o.view(torch.bfloat16)[:arena] for o in out32]
+    r16_med, r16_min = time_kernel(lambda: L.retrieve_grads(s0[1], out16, 0.125, odc.ODC_OUT_BF16), torch)
+    del out32, out16
     nbytes_copy = (full.numel() * 2) // 16 * 16
     scratch = torch.empty_like(full)
     cp_med, cp_min = time_kernel(lambda: odc.probe_copy(scratch, full, nbytes_copy), torch)
@@ -288,6 +295,9 @@ def main():
             "scatter_accumulate_GBs": {"median": round(10 * total / acc_med / 1e6, 1), "best": round(10 * total / acc_min / 1e6, 1)},
             "gather_GBs": {"median": round(4 * total / gat_med / 1e6, 1), "best": round(4 * total / gat_min / 1e6, 1)},
             "reset_GBs": {"median": round(4 * total / rst_med / 1e6, 1), "best": round(4 * total / rst_min / 1e6, 1)},
+            "scatter_accumulate_weighted_GBs": {"median": round(10 * total / wac_med / 1e6, 1), "best": round(10 * total / wac_min / 1e6, 1)},
+            "retrieve_f32_GBs": {"median": round(8 * total / r32_med / 1e6, 1), "best": round(8 * total / r32_min / 1e6, 1)},
+            "retrieve_bf16_GBs": {"median": round(6 * total / r16_med / 1e6, 1), "best": round(6 * total / r16_min / 1e6, 1)},
             "plain_copy_GBs": {"median": round(2 * nbytes_copy / cp_med / 1e6, 1), "best": round(2 * nbytes_copy / cp_min / 1e6, 1)},
         },
     }
@@ -302,10 +312,13 @@ def main():
 _seq = [0]
 
 
-def _accum_once(L, g, acc, odc):
+def _accum_once(L, g, acc, odc, weight=None):
     """One ordered contribution with a fresh (worker 0, microbatch k) slot."""
     _seq[0] += 1
-    L.scatter_accumulate(g, acc, 0, _seq[0], odc.ODC_ORDERED)
+    if weight is None:
+        L.scatter_accumulate(g, acc, 0, _seq[0], odc.ODC_ORDERED)
+    else:
+        L.scatter_accumulate_weighted(g, acc, 0, _seq[0], weight, odc.ODC_ORDERED)
 
 
 if __name__ == "__main__":

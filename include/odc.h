@@ -128,6 +128,39 @@ int odc_scatter_accumulate(const odc_layout_t *layout, const void *grad_full,
                            void *stream);
 
 /*
+ * Weighted contribution (Section 2.1: the accumulated gradient is the sum of w_m * g^(m), with
+ * w_m = 1 for a plain sum or a token- or sample-proportional weight for an average).  Same
+ * arguments, ordering rules and history as odc_scatter_accumulate, plus `weight`:
+ *   accum_shards[r][shard_off_t + i] = fma32(weight, widen(grad_full[...]), accum_shards[r][...])
+ * one fused multiply-add per element, i.e. a single rounding of weight*g + acc (the paper does
+ * not fix the rounding; this is the reading taken).  With weight = 1 the result is that of
+ * odc_scatter_accumulate bit for bit.  ODC_UNORDERED rounds the product first and adds it
+ * atomically.  Algorithmic HBM traffic: 10 bytes per valid element.
+ */
+int odc_scatter_accumulate_weighted(const odc_layout_t *layout, const void *grad_full,
+                                    void *const *accum_shards, int worker, int microbatch,
+                                    float weight, int flags, void *stream);
+
+/* odc_retrieve_grads output types */
+#define ODC_OUT_F32 0
+#define ODC_OUT_BF16 1
+
+/*
+ * Minibatch end (Section 3.2: the integration retrieves the accumulated gradients at the
+ * minibatch end; each owner then holds what reduce-scatter would have left on it, Section 2.2).
+ *   out_shards[r][shard_off_t + i] = cast(fl32(scale * accum_shards[r][shard_off_t + i]))   i < valid(t, r)
+ * one binary32 multiplication (scale = 1 for a sum, 1/tokens or 1/samples for an average), then
+ * no further rounding (ODC_OUT_F32, out_shards are binary32) or one rounding to nearest-even to
+ * bf16 (ODC_OUT_BF16; NaN stays NaN).  The accumulators are not modified and the ordered-mode
+ * history is kept; call odc_reset_accum before the next minibatch.
+ *   accum_shards  [R] host array of device pointers, binary32, read only
+ *   out_shards    [R] host array of device pointers, >= odc_rank_arena_elems elements each, 16-byte aligned
+ * Algorithmic HBM traffic: 8 (binary32 out) or 6 (bf16 out) bytes per valid element.
+ */
+int odc_retrieve_grads(const odc_layout_t *layout, const void *const *accum_shards,
+                       void *const *out_shards, float scale, int out_dtype, void *stream);
+
+/*
  * Start of a minibatch (Section 3.2: accumulated gradients are retrieved at the minibatch
  * end, so accumulators are cleared before the next one): every valid accumulator element
  * becomes +0.0f.  Also clears the ordered-mode history of this accumulator set.

@@ -24,12 +24,14 @@ ODC_MAX_RANKS = 4096
 ODC_LAYOUT_HOST_ONLY = 1
 ODC_ORDERED = 0
 ODC_UNORDERED = 1
+ODC_OUT_F32 = 0
+ODC_OUT_BF16 = 1
 
 EXPORTS = (
     "odc_init_layout", "odc_free_layout", "odc_num_ranks", "odc_num_tensors", "odc_numel",
     "odc_shard_elems", "odc_valid_elems", "odc_rank_arena_elems", "odc_full_elems",
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
-    "odc_reset_accum", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_retrieve_grads", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
 _i64 = ctypes.c_int64
@@ -80,6 +82,11 @@ def lib():
         L.odc_gather.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp]
         L.odc_scatter_accumulate.restype = _int
         L.odc_scatter_accumulate.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _int, _int, _int, _vp]
+        L.odc_scatter_accumulate_weighted.restype = _int
+        L.odc_scatter_accumulate_weighted.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _int, _int, ctypes.c_float,
+                                                      _int, _vp]
+        L.odc_retrieve_grads.restype = _int
+        L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
         L.odc_reset_accum.argtypes = [_vp, ctypes.POINTER(_vp), _vp]
         L.odc_strerror.restype = ctypes.c_char_p
@@ -210,6 +217,20 @@ class Layout:
         if rc != ODC_OK:
             raise OdcError(rc, "odc_scatter_accumulate")
 
+    def scatter_accumulate_weighted(self, grad_full, accum_shards, worker: int, microbatch: int, weight: float,
+                                    flags: int = ODC_ORDERED, stream=None) -> None:
+        rc = lib().odc_scatter_accumulate_weighted(self.handle, _ptr(grad_full), _ptr_array(accum_shards, self.R),
+                                                   int(worker), int(microbatch), float(weight), int(flags),
+                                                   _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_scatter_accumulate_weighted")
+
+    def retrieve_grads(self, accum_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
+                       stream=None) -> None:
+        rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_retrieve_grads")
+
     def reset_accum(self, accum_shards, stream=None) -> None:
         rc = reset_accum_rc(self, accum_shards, stream)
         if rc != ODC_OK:
@@ -227,6 +248,13 @@ def scatter_accumulate_rc(layout: Layout, grad_full, accum_shards, worker: int, 
     return lib().odc_scatter_accumulate(layout.handle, _ptr(grad_full),
                                         _ptr_array(accum_shards, layout.R), int(worker),
                                         int(microbatch), int(flags), _stream(stream))
+
+
+def retrieve_grads_rc(layout: Layout, accum_shards, out_shards, scale: float = 1.0,
+                      out_dtype: int = ODC_OUT_F32, stream=None) -> int:
+    return lib().odc_retrieve_grads(layout.handle, _ptr_array(accum_shards, layout.R),
+                                    _ptr_array(out_shards, layout.R), float(scale), int(out_dtype),
+                                    _stream(stream))
 
 
 def reset_accum_rc(layout: Layout, accum_shards, stream=None) -> int:

@@ -19,7 +19,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wextra", "-Wshadow", "-Wno-unused-command-line-argument",
 ]
 
 

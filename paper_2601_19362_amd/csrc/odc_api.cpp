@@ -170,8 +170,10 @@ int odc_gather(const odc_layout_t *L, const void *const *param_shards, void *ful
     return ODC_OK;
 }
 
-int odc_scatter_accumulate(const odc_layout_t *L, const void *grad_full, void *const *accum_shards,
-                           int worker, int microbatch, int flags, void *stream)
+// Common body of the unweighted and the weighted contribution.
+static int scatter_accumulate_impl(const odc_layout_t *L, const void *grad_full, void *const *accum_shards,
+                                   int worker, int microbatch, bool weighted, float weight, int flags,
+                                   void *stream)
 {
     int rc = check_launchable(L, accum_shards);
     if (rc != ODC_OK) return rc;
@@ -206,10 +208,10 @@ int odc_scatter_accumulate(const odc_layout_t *L, const void *grad_full, void *c
         int e;
         if (H.T == 1)
             e = odc::launch_accum_flat(accum_shards + r0, r0, nr, grad_full, H.desc[0].S,
-                                       H.desc[0].numel, atomic, stream);
+                                       H.desc[0].numel, atomic, weighted, weight, stream);
         else
-            e = odc::launch_accum_batched(L->table, accum_shards + r0, r0, nr, grad_full, atomic,
-                                          stream);
+            e = odc::launch_accum_batched(L->table, accum_shards + r0, r0, nr, grad_full, atomic, weighted,
+                                          weight, stream);
         if (e != 0) rc = hip_fail(static_cast<hipError_t>(e));
         else if (slot) {
             *slot = now;  // something was enqueued: this contribution counts as issued
@@ -218,6 +220,44 @@ int odc_scatter_accumulate(const odc_layout_t *L, const void *grad_full, void *c
     }
     if (inserted) M->last.erase(accum_shards[0]);  // nothing was enqueued
     return rc;
+}
+
+int odc_scatter_accumulate(const odc_layout_t *L, const void *grad_full, void *const *accum_shards,
+                           int worker, int microbatch, int flags, void *stream)
+{
+    return scatter_accumulate_impl(L, grad_full, accum_shards, worker, microbatch, false, 1.0f, flags, stream);
+}
+
+int odc_scatter_accumulate_weighted(const odc_layout_t *L, const void *grad_full, void *const *accum_shards,
+                                    int worker, int microbatch, float weight, int flags, void *stream)
+{
+    return scatter_accumulate_impl(L, grad_full, accum_shards, worker, microbatch, true, weight, flags, stream);
+}
+
+int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, void *const *out_shards,
+                       float scale, int out_dtype, void *stream)
+{
+    int rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    rc = check_launchable(L, out_shards);
+    if (rc != ODC_OK) return rc;
+    if (out_dtype != ODC_OUT_F32 && out_dtype != ODC_OUT_BF16) return ODC_ERR_INVALID_ARG;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    const bool bf16 = out_dtype == ODC_OUT_BF16;
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_retrieve_flat(accum_shards + r0, out_shards + r0, r0, nr, H.desc[0].S,
+                                          H.desc[0].numel, scale, bf16, stream);
+        else
+            e = odc::launch_retrieve_batched(L->table, accum_shards + r0, out_shards + r0, r0, nr, scale,
+                                             bf16, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    return ODC_OK;
 }
 
 int odc_reset_accum(const odc_layout_t *L, void *const *accum_shards, void *stream)

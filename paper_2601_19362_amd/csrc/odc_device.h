@@ -92,10 +92,11 @@ __device__ __forceinline__ float widen_lo(uint32_t two) { return __uint_as_float
 __device__ __forceinline__ float widen_hi(uint32_t two) { return __uint_as_float(two & 0xFFFF0000u); }
 __device__ __forceinline__ float widen_one(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
-template <bool ATOMIC>
-__device__ __forceinline__ void add_one(float *a, float v)
+template <bool ATOMIC, bool WEIGHTED>
+__device__ __forceinline__ void add_one(float *a, float v, float w)
 {
-    if constexpr (ATOMIC) unsafeAtomicAdd(a, v);
+    if constexpr (ATOMIC) unsafeAtomicAdd(a, WEIGHTED ? w * v : v);
+    else if constexpr (WEIGHTED) st_f32(a, __builtin_fmaf(w, v, ld_f32(a)));
     else st_f32(a, ld_f32(a) + v);
 }
 
@@ -174,29 +175,43 @@ __global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *
     }
 }
 
-__device__ __forceinline__ f32x4 add4(f32x4 a, u32x2 g)
+// Ordered contribution to four accumulator elements.  Unweighted (Section 2.1 with w_m = 1):
+// one binary32 add each.  Weighted: one fused multiply-add each, acc = fma(w, g, acc), a
+// single rounding of w*g + acc.
+template <bool WEIGHTED>
+__device__ __forceinline__ f32x4 add4(f32x4 a, u32x2 g, float w)
 {
-    a.x = a.x + widen_lo(g.x);
-    a.y = a.y + widen_hi(g.x);
-    a.z = a.z + widen_lo(g.y);
-    a.w = a.w + widen_hi(g.y);
+    if constexpr (WEIGHTED) {
+        a.x = __builtin_fmaf(w, widen_lo(g.x), a.x);
+        a.y = __builtin_fmaf(w, widen_hi(g.x), a.y);
+        a.z = __builtin_fmaf(w, widen_lo(g.y), a.z);
+        a.w = __builtin_fmaf(w, widen_hi(g.y), a.w);
+    } else {
+        a.x = a.x + widen_lo(g.x);
+        a.y = a.y + widen_hi(g.x);
+        a.z = a.z + widen_lo(g.y);
+        a.w = a.w + widen_hi(g.y);
+    }
     return a;
 }
 
-__device__ __forceinline__ void atomic_add4(float *a, u32x2 g)
+// Unordered contribution: device-scope float atomics (the weighted product is rounded first).
+template <bool WEIGHTED>
+__device__ __forceinline__ void atomic_add4(float *a, u32x2 g, float w)
 {
-    unsafeAtomicAdd(a + 0, widen_lo(g.x));
-    unsafeAtomicAdd(a + 1, widen_hi(g.x));
-    unsafeAtomicAdd(a + 2, widen_lo(g.y));
-    unsafeAtomicAdd(a + 3, widen_hi(g.y));
+    const float s = WEIGHTED ? w : 1.0f;
+    unsafeAtomicAdd(a + 0, WEIGHTED ? s * widen_lo(g.x) : widen_lo(g.x));
+    unsafeAtomicAdd(a + 1, WEIGHTED ? s * widen_hi(g.x) : widen_hi(g.x));
+    unsafeAtomicAdd(a + 2, WEIGHTED ? s * widen_lo(g.y) : widen_lo(g.y));
+    unsafeAtomicAdd(a + 3, WEIGHTED ? s * widen_hi(g.y) : widen_hi(g.y));
 }
 
 // A work item is one accumulator vector (4 floats, 16 bytes) and 8 bytes of gradient;
 // consecutive lanes take consecutive vectors, so every wave instruction is contiguous
 // (1 KiB of accumulator, 512 B of gradient).
-template <int TPB, int U, bool NT, bool ATOMIC, bool GUARD>
+template <int TPB, int U, bool NT, bool ATOMIC, bool WEIGHTED, bool GUARD>
 __device__ __forceinline__ void accum_tile(float *__restrict__ acc, const uint16_t *__restrict__ g,
-                                           int64_t q0, int64_t nitem)
+                                           int64_t q0, int64_t nitem, float w)
 {
     f32x4 *__restrict__ accv = reinterpret_cast<f32x4 *>(acc);
     u32x2 gv[U];
@@ -213,15 +228,15 @@ __device__ __forceinline__ void accum_tile(float *__restrict__ acc, const uint16
     for (int u = 0; u < U; ++u) {
         const int64_t q = q0 + u * TPB;
         if (!GUARD || q < nitem) {
-            if constexpr (ATOMIC) atomic_add4(acc + 4 * q, gv[u]);
-            else st<NT>(accv + q, add4(av[u], gv[u]));
+            if constexpr (ATOMIC) atomic_add4<WEIGHTED>(acc + 4 * q, gv[u], w);
+            else st<NT>(accv + q, add4<WEIGHTED>(av[u], gv[u], w));
         }
     }
 }
 
-template <int TPB, int U, bool NT, bool ATOMIC>
+template <int TPB, int U, bool NT, bool ATOMIC, bool WEIGHTED>
 __global__ __launch_bounds__(TPB) void k_accum_flat(RankPtrs accs, const uint16_t *__restrict__ grad,
-                                                    int64_t S, int64_t N, int r0, int remap)
+                                                    int64_t S, int64_t N, int r0, int remap, float w)
 {
     const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
     int64_t valid = N - base;
@@ -236,12 +251,12 @@ __global__ __launch_bounds__(TPB) void k_accum_flat(RankPtrs accs, const uint16_
     const int64_t nslots = slots_of(ntiles, remap);
     for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
         const int64_t t0 = tile_of(slot, ntiles, remap) * (TPB * U);
-        if (t0 + TPB * U <= nitem) accum_tile<TPB, U, NT, ATOMIC, false>(acc, g, t0 + threadIdx.x, nitem);
-        else if (t0 < nitem) accum_tile<TPB, U, NT, ATOMIC, true>(acc, g, t0 + threadIdx.x, nitem);
+        if (t0 + TPB * U <= nitem) accum_tile<TPB, U, NT, ATOMIC, WEIGHTED, false>(acc, g, t0 + threadIdx.x, nitem, w);
+        else if (t0 < nitem) accum_tile<TPB, U, NT, ATOMIC, WEIGHTED, true>(acc, g, t0 + threadIdx.x, nitem, w);
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
         const int64_t k = 4 * nitem + threadIdx.x;
-        add_one<ATOMIC>(acc + k, widen_one(ld_u16(g + k)));
+        add_one<ATOMIC, WEIGHTED>(acc + k, widen_one(ld_u16(g + k)), w);
     }
 }
 
@@ -681,20 +696,21 @@ __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc 
     }
 }
 
-template <bool NT, bool ATOMIC>
-__device__ __forceinline__ void accum_item_store(const AccumItem &it)
+template <bool NT, bool ATOMIC, bool WEIGHTED>
+__device__ __forceinline__ void accum_item_store(const AccumItem &it, float w)
 {
     if (it.cnt == 0) return;
     if constexpr (ATOMIC) {
         if (it.cnt == 4) {
-            atomic_add4(it.ap, it.g);
+            atomic_add4<WEIGHTED>(it.ap, it.g, w);
         } else {
-            unsafeAtomicAdd(it.ap, widen_lo(it.g.x));
-            if (it.cnt > 1) unsafeAtomicAdd(it.ap + 1, widen_hi(it.g.x));
-            if (it.cnt > 2) unsafeAtomicAdd(it.ap + 2, widen_lo(it.g.y));
+            const float s = WEIGHTED ? w : 1.0f;
+            unsafeAtomicAdd(it.ap, WEIGHTED ? s * widen_lo(it.g.x) : widen_lo(it.g.x));
+            if (it.cnt > 1) unsafeAtomicAdd(it.ap + 1, WEIGHTED ? s * widen_hi(it.g.x) : widen_hi(it.g.x));
+            if (it.cnt > 2) unsafeAtomicAdd(it.ap + 2, WEIGHTED ? s * widen_lo(it.g.y) : widen_lo(it.g.y));
         }
     } else {
-        const f32x4 sum = add4(it.acc, it.g);  // lanes beyond cnt are computed but never stored
+        const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);  // lanes beyond cnt are computed but never stored
         if (it.cnt == 4) {
             st<NT>(reinterpret_cast<f32x4 *>(it.ap), sum);
         } else {
@@ -706,18 +722,19 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it)
 }
 
 // One-dimensional grid over (tile of the rank arena, group of RG owners), group fastest.
-template <int RG, bool NT, bool ATOMIC>
+template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
 __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, RankPtrs accs,
-                                                                 const uint16_t *__restrict__ grad, int r0, int nr)
+                                                                 const uint16_t *__restrict__ grad, int r0, int nr,
+                                                                 float w)
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
     const int ngroups = (nr + RG - 1) / RG;
     const int64_t nwork = ntiles * ngroups;
-    for (int64_t w = blockIdx.x; w < nwork; w += gridDim.x) {
-        if (w != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = w / ngroups;
-        const int rl0 = static_cast<int>(w - tile * ngroups) * RG;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / ngroups;
+        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
         AccumItem items[kAccumItems][RG];
@@ -739,7 +756,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u)
 #pragma unroll
-            for (int k = 0; k < RG; ++k) accum_item_store<NT, ATOMIC>(items[u][k]);
+            for (int k = 0; k < RG; ++k) accum_item_store<NT, ATOMIC, WEIGHTED>(items[u][k], w);
     }
 }
 
@@ -751,10 +768,10 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
     const int ngroups = (nr + RG - 1) / RG;
     const int64_t nwork = ntiles * ngroups;
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int64_t w = blockIdx.x; w < nwork; w += gridDim.x) {
-        if (w != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = w / ngroups;
-        const int rl0 = static_cast<int>(w - tile * ngroups) * RG;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / ngroups;
+        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
@@ -772,6 +789,103 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
                 if (cnt == 4) st<NT>(reinterpret_cast<f32x4 *>(arena + a), zero);
                 else
                     for (int e = 0; e < cnt; ++e) st_f32(arena + a + e, 0.0f);
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------- retrieve
+// Minibatch-end retrieval (paper Section 3.2): each owner's accumulated gradient shard is
+// read, multiplied by `scale` (one binary32 multiply) and written to the owner's output shard
+// as binary32 or, rounded once more to nearest-even, as bf16.  4 + 4 or 4 + 2 bytes per
+// element; the accumulators are left as they are.
+
+// binary32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t narrow_bf16(float f)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <bool NT, bool BF16>
+__device__ __forceinline__ void retrieve_vec(const float *__restrict__ src, void *__restrict__ out, int64_t q, float scale)
+{
+    f32x4 v = ld<NT>(reinterpret_cast<const f32x4 *>(src) + q);
+    v.x = scale * v.x;
+    v.y = scale * v.y;
+    v.z = scale * v.z;
+    v.w = scale * v.w;
+    if constexpr (BF16) {
+        const u32x2 p = {narrow_bf16(v.x) | (narrow_bf16(v.y) << 16), narrow_bf16(v.z) | (narrow_bf16(v.w) << 16)};
+        st<NT>(reinterpret_cast<u32x2 *>(out) + q, p);
+    } else {
+        st<NT>(reinterpret_cast<f32x4 *>(out) + q, v);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void retrieve_one(const float *src, void *out, int64_t k, float scale)
+{
+    const float v = scale * ld_f32(src + k);
+    if constexpr (BF16) st_u16(static_cast<uint16_t *>(out) + k, static_cast<uint16_t>(narrow_bf16(v)));
+    else st_f32(static_cast<float *>(out) + k, v);
+}
+
+template <int TPB, int U, bool NT, bool BF16>
+__global__ __launch_bounds__(TPB) void k_retrieve_flat(RankPtrs accs, RankPtrs outs, int64_t S, int64_t N, int r0,
+                                                       float scale)
+{
+    const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
+    int64_t valid = N - base;
+    if (valid > S) valid = S;
+    if (valid <= 0) return;
+    const float *__restrict__ acc = static_cast<const float *>(accs.p[blockIdx.y]);
+    void *__restrict__ out = outs.p[blockIdx.y];
+    const int64_t nvec = valid >> 2;
+    const int tail = static_cast<int>(valid & 3);
+    const int64_t ntiles = (nvec + TPB * U - 1) / (TPB * U);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t v0 = tile * (TPB * U) + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t v = v0 + u * TPB;
+            if (v < nvec) retrieve_vec<NT, BF16>(acc, out, v, scale);
+        }
+    }
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) retrieve_one<BF16>(acc, out, 4 * nvec + threadIdx.x, scale);
+}
+
+template <int RG, bool NT, bool BF16>
+__global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable tb, RankPtrs accs, RankPtrs outs,
+                                                                    int r0, int nr, float scale)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int ngroups = (nr + RG - 1) / RG;
+    const int64_t nwork = ntiles * ngroups;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / ngroups;
+        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = (tile << kChunkShift) + a_rel;
+            if (a >= tb.arena_elems) continue;
+            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+#pragma unroll
+            for (int k = 0; k < RG; ++k) {
+                const int rl = rl0 + k;
+                if (rl >= nr) continue;
+                const float *src = static_cast<const float *>(accs.p[rl]);
+                void *out = outs.p[rl];
+                const int cnt = valid_from(d, r0 + rl, a - d.shard_off, 4);
+                if (cnt == 4) retrieve_vec<NT, BF16>(src, out, a >> 2, scale);
+                else
+                    for (int e = 0; e < cnt; ++e) retrieve_one<BF16>(src, out, a + e, scale);
             }
         }
     }

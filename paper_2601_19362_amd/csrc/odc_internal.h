@@ -96,7 +96,7 @@ Tuning &tuning();
 int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int64_t S, int64_t N,
                        void *stream);
 int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64_t S, int64_t N,
-                      bool atomic, void *stream);
+                      bool atomic, bool weighted, float w, void *stream);
 int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, void *stream);
 int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr,
                           void *full, void *stream);
@@ -106,7 +106,11 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
 // 2^kChunkShift / kAlignElems tensors; the host layout checks this bound.
 constexpr int kMaxTensorsPerChunk = (1 << kChunkShift) / static_cast<int>(kAlignElems);
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr,
-                         const void *grad, bool atomic, void *stream);
+                         const void *grad, bool atomic, bool weighted, float w, void *stream);
+int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
+                         float scale, bool bf16, void *stream);
+int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,
+                            float scale, bool bf16, void *stream);
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream);
 int launch_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
 

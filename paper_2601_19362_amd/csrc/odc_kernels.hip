@@ -28,6 +28,11 @@ dim3 grid_for(int64_t items, int per_block, int nr)
     return dim3(gx, static_cast<unsigned>(nr), 1);
 }
 
+dim3 plain_grid(int64_t items, int per_block, int nr)
+{
+    return dim3(grid_x_for(items, per_block, tuning().max_grid_x), static_cast<unsigned>(nr), 1);
+}
+
 int finish() { return static_cast<int>(hipGetLastError()); }
 
 // Dispatch runtime (threads, unroll, non-temporal) to the matching instantiation.  Inside
@@ -71,21 +76,21 @@ int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int6
 }
 
 int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64_t S, int64_t N,
-                      bool atomic, void *stream)
+                      bool atomic, bool weighted, float w, void *stream)
 {
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
-    if (atomic) {
-        ODC_DISPATCH(t.accum_threads, t.accum_unroll, false,
-                     (k_accum_flat<TPB_, U_, NT_, true><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
-                         rp, g, S, N, r0, t.tile_remap)));
-    } else {
-        ODC_DISPATCH(t.accum_threads, t.accum_unroll, t.nontemporal != 0,
-                     (k_accum_flat<TPB_, U_, NT_, false><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
-                         rp, g, S, N, r0, t.tile_remap)));
-    }
+#define ODC_ACCUM_FLAT(ATOMIC_, WEIGHTED_, NTF)                                                                 \
+    ODC_DISPATCH(t.accum_threads, t.accum_unroll, NTF,                                                          \
+                 (k_accum_flat<TPB_, U_, NT_, ATOMIC_, WEIGHTED_><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>( \
+                     rp, g, S, N, r0, t.tile_remap, w)))
+    if (atomic && weighted) ODC_ACCUM_FLAT(true, true, false);
+    else if (atomic) ODC_ACCUM_FLAT(true, false, false);
+    else if (weighted) ODC_ACCUM_FLAT(false, true, t.nontemporal != 0);
+    else ODC_ACCUM_FLAT(false, false, t.nontemporal != 0);
+#undef ODC_ACCUM_FLAT
     return finish();
 }
 
@@ -141,7 +146,7 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
 }
 
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *grad,
-                         bool atomic, void *stream)
+                         bool atomic, bool weighted, float w, void *stream)
 {
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -149,15 +154,15 @@ int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
     const int rg = rank_group(tiles, nr);
     const int64_t work = tiles * ((nr + rg - 1) / rg);
-    if (atomic) {
-        ODC_DISPATCH_RG(rg, false,
-                        (k_accum_batched<RG_, NT_, true><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
-                            tb, rp, g, r0, nr)));
-    } else {
-        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
-                        (k_accum_batched<RG_, NT_, false><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
-                            tb, rp, g, r0, nr)));
-    }
+#define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                                   \
+    ODC_DISPATCH_RG(rg, NTF,                                                                                         \
+                    (k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>( \
+                        tb, rp, g, r0, nr, w)))
+    if (atomic && weighted) ODC_ACCUM_BATCHED(true, true, false);
+    else if (atomic) ODC_ACCUM_BATCHED(true, false, false);
+    else if (weighted) ODC_ACCUM_BATCHED(false, true, tuning().nontemporal != 0);
+    else ODC_ACCUM_BATCHED(false, false, tuning().nontemporal != 0);
+#undef ODC_ACCUM_BATCHED
     return finish();
 }
 
@@ -170,6 +175,46 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const int64_t work = tiles * ((nr + rg - 1) / rg);
     ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
                     (k_reset_batched<RG_, NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
+    return finish();
+}
+
+int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
+                         float scale, bool bf16, void *stream)
+{
+    const Tuning &t = tuning();
+    const RankPtrs ra = pack(acc, nr);
+    const RankPtrs ro = pack(out, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (bf16) {
+        ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
+                     (k_retrieve_flat<TPB_, U_, NT_, true><<<plain_grid((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         ra, ro, S, N, r0, scale)));
+    } else {
+        ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
+                     (k_retrieve_flat<TPB_, U_, NT_, false><<<plain_grid((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         ra, ro, S, N, r0, scale)));
+    }
+    return finish();
+}
+
+int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,
+                            float scale, bool bf16, void *stream)
+{
+    const RankPtrs ra = pack(acc, nr);
+    const RankPtrs ro = pack(out, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int rg = rank_group(tiles, nr);
+    const int64_t work = tiles * ((nr + rg - 1) / rg);
+    if (bf16) {
+        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+                        (k_retrieve_batched<RG_, NT_, true><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                            tb, ra, ro, r0, nr, scale)));
+    } else {
+        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+                        (k_retrieve_batched<RG_, NT_, false><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                            tb, ra, ro, r0, nr, scale)));
+    }
     return finish();
 }
 

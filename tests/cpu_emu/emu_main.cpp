@@ -5,9 +5,9 @@
 // rank buffer is its own exactly-sized heap block, so any access outside the valid range of
 // a buffer is reported.  The test compares the outputs with the CPU oracle.
 //
-// usage: emu <dir> <op> <R> <threads> <unroll> <nt> <remap> <atomic> <grid_cap> <rank_group>
+// usage: emu <dir> <op> <R> [threads= unroll= nt= remap= atomic= cap= rg= weighted= weight= bf16= scale=]
 //   dir holds numel.i64 [T]; arenas.u16 [R*arena] (gather); full.u16 [full] (gather in/out);
-//   grad.u16 [full] and acc.f32 [R*arena] (accum / reset, in/out)
+//   grad.u16 [full] and acc.f32 [R*arena] (accum / reset, in/out; retrieve: in, with out.bin [R*arena] in/out)
 #include "hip_shim.h"
 
 #include <cstdio>
@@ -135,14 +135,35 @@ unsigned gx_for(int64_t items, int per_block, int cap, int remap)
 
 int main(int argc, char **argv)
 {
-    if (argc != 11) {
-        std::fprintf(stderr, "usage: emu dir op R threads unroll nt remap atomic grid_cap rank_group\n");
+    if (argc < 4) {
+        std::fprintf(stderr, "usage: emu dir op R [key=value ...]\n");
         return 2;
     }
     const std::string dir = argv[1], op = argv[2];
-    const int R = std::atoi(argv[3]), threads = std::atoi(argv[4]), unroll = std::atoi(argv[5]);
-    const int nt = std::atoi(argv[6]), remap = std::atoi(argv[7]), atomic = std::atoi(argv[8]);
-    const int cap = std::atoi(argv[9]), rg = std::atoi(argv[10]);
+    const int R = std::atoi(argv[3]);
+    int threads = 256, unroll = 4, nt = 1, remap = 0, atomic = 0, cap = 0, rg = 1, weighted = 0, bf16 = 0;
+    float weight = 1.0f, scale = 1.0f;
+    for (int k = 4; k < argc; ++k) {
+        const std::string kv = argv[k];
+        const size_t eq = kv.find('=');
+        if (eq == std::string::npos) return 2;
+        const std::string key = kv.substr(0, eq), val = kv.substr(eq + 1);
+        if (key == "threads") threads = std::atoi(val.c_str());
+        else if (key == "unroll") unroll = std::atoi(val.c_str());
+        else if (key == "nt") nt = std::atoi(val.c_str());
+        else if (key == "remap") remap = std::atoi(val.c_str());
+        else if (key == "atomic") atomic = std::atoi(val.c_str());
+        else if (key == "cap") cap = std::atoi(val.c_str());
+        else if (key == "rg") rg = std::atoi(val.c_str());
+        else if (key == "weighted") weighted = std::atoi(val.c_str());
+        else if (key == "bf16") bf16 = std::atoi(val.c_str());
+        else if (key == "weight") weight = std::strtof(val.c_str(), nullptr);
+        else if (key == "scale") scale = std::strtof(val.c_str(), nullptr);
+        else {
+            std::fprintf(stderr, "unknown key %s\n", key.c_str());
+            return 2;
+        }
+    }
     using namespace odc;
 
     std::vector<int64_t> numel = read_file<int64_t>(dir + "/numel.i64");
@@ -222,28 +243,26 @@ int main(int argc, char **argv)
                                                      [&] { k_reset_batched<RG_, NT_>(tb, rp, r0, nr); }));
                 }
             } else if (flat) {
-                if (atomic) {
-                    EMU_DISPATCH(threads, unroll, 0,
-                                 run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr, [&] {
-                                     k_accum_flat<TPB_, U_, NT_, true>(rp, grad, S, N, r0, remap);
-                                 }));
-                } else {
-                    EMU_DISPATCH(threads, unroll, nt,
-                                 run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr, [&] {
-                                     k_accum_flat<TPB_, U_, NT_, false>(rp, grad, S, N, r0, remap);
-                                 }));
-                }
+#define EMU_ACC_FLAT(ATOMIC_, WEIGHTED_, NTF)                                                        \
+    EMU_DISPATCH(threads, unroll, NTF, run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr, [&] { \
+                     k_accum_flat<TPB_, U_, NT_, ATOMIC_, WEIGHTED_>(rp, grad, S, N, r0, remap, weight);  \
+                 }))
+                if (atomic && weighted) EMU_ACC_FLAT(true, true, 0);
+                else if (atomic) EMU_ACC_FLAT(true, false, 0);
+                else if (weighted) EMU_ACC_FLAT(false, true, nt);
+                else EMU_ACC_FLAT(false, false, nt);
+#undef EMU_ACC_FLAT
             } else {
                 const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
-                if (atomic) {
-                    EMU_RG(rg, 0, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
-                               k_accum_batched<RG_, NT_, true>(tb, rp, grad, r0, nr);
-                           }));
-                } else {
-                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
-                               k_accum_batched<RG_, NT_, false>(tb, rp, grad, r0, nr);
-                           }));
-                }
+#define EMU_ACC_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                   \
+    EMU_RG(rg, NTF, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {               \
+               k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_>(tb, rp, grad, r0, nr, weight);         \
+           }))
+                if (atomic && weighted) EMU_ACC_BATCHED(true, true, 0);
+                else if (atomic) EMU_ACC_BATCHED(true, false, 0);
+                else if (weighted) EMU_ACC_BATCHED(false, true, nt);
+                else EMU_ACC_BATCHED(false, false, nt);
+#undef EMU_ACC_BATCHED
             }
         }
         std::vector<float> out(arena * static_cast<size_t>(R));
@@ -253,6 +272,63 @@ int main(int argc, char **argv)
         std::free(grad);
         return 0;
     }
+    if (op == "retrieve") {
+        std::vector<float> all = read_file<float>(dir + "/acc.f32");
+        if (all.size() != arena * static_cast<size_t>(R)) return 4;
+        const size_t esz = bf16 ? 2 : 4;
+        std::vector<char> out_in = read_file<char>(dir + "/out.bin");
+        if (out_in.size() != arena * esz * static_cast<size_t>(R)) return 4;
+        std::vector<float *> accs(static_cast<size_t>(R));
+        std::vector<char *> outs(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            accs[r] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(accs[r], all.data() + arena * r, arena * 4);
+            outs[r] = static_cast<char *>(std::malloc(arena * esz));
+            std::memcpy(outs[r], out_in.data() + arena * esz * r, arena * esz);
+        }
+        for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+            const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+            RankPtrs ra{}, ro{};
+            for (int k = 0; k < nr; ++k) {
+                ra.p[k] = accs[r0 + k];
+                ro.p[k] = outs[r0 + k];
+            }
+            if (flat) {
+                if (bf16) {
+                    EMU_DISPATCH(threads, unroll, nt, run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, 0), nr, [&] {
+                                     k_retrieve_flat<TPB_, U_, NT_, true>(ra, ro, S, N, r0, scale);
+                                 }));
+                } else {
+                    EMU_DISPATCH(threads, unroll, nt, run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, 0), nr, [&] {
+                                     k_retrieve_flat<TPB_, U_, NT_, false>(ra, ro, S, N, r0, scale);
+                                 }));
+                }
+            } else {
+                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
+                if (bf16) {
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                               k_retrieve_batched<RG_, NT_, true>(tb, ra, ro, r0, nr, scale);
+                           }));
+                } else {
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                               k_retrieve_batched<RG_, NT_, false>(tb, ra, ro, r0, nr, scale);
+                           }));
+                }
+            }
+        }
+        std::vector<char> out(arena * esz * static_cast<size_t>(R));
+        std::vector<float> acc_after(arena * static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            std::memcpy(out.data() + arena * esz * r, outs[r], arena * esz);
+            std::memcpy(acc_after.data() + arena * r, accs[r], arena * 4);
+        }
+        write_file(dir + "/out.out", out.data(), out.size());
+        write_file(dir + "/acc.out", acc_after.data(), acc_after.size());
+        for (auto *b : accs) std::free(b);
+        for (auto *b : outs) std::free(b);
+        return 0;
+    }
+
     std::fprintf(stderr, "unknown op %s\n", op.c_str());
     return 2;
 }

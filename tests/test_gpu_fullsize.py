@@ -61,6 +61,38 @@ def full_layer_case(oracle, N, R, contribs, seed, prange=(-0.05, 0.05), sigma=1e
     L.close()
 
 
+def test_7b_layer_weighted_and_retrieve(oracle):
+    """Weighted contributions and both retrieval forms at the 7B layer shape."""
+    w = inputs.workload("7b")
+    N, R = w.numel[0], w.R
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    acc = [torch.full((S,), 3.25, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc_h = [np.full(S, 3.25, dtype=np.float32) for _ in range(R)]
+    L.reset_accum(acc)
+    oracle.reset(acc_h, N, nthreads=THREADS)
+    for k, wt in enumerate((0.37, 1.0 / 3.0)):
+        g = inputs.device_normal_bf16(N, 1e-3, 900 + k, dev)
+        L.scatter_accumulate_weighted(g, acc, 2, k, wt)
+        oracle.accumulate_weighted(g.view(torch.int16).cpu().numpy().view(np.uint16), acc_h, N, wt, nthreads=THREADS)
+    for r in range(R):
+        assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"weighted accumulate rank {r}")
+    scale = 1.0 / 4096.0 * 3.0
+    out32 = [torch.zeros(S, dtype=torch.float32, device=dev) for _ in range(R)]
+    out16 = [torch.zeros(S, dtype=torch.int16, device=dev) for _ in range(R)]
+    L.retrieve_grads(acc, out32, scale, odc.ODC_OUT_F32)
+    L.retrieve_grads(acc, out16, scale, odc.ODC_OUT_BF16)
+    w32 = [np.zeros(S, dtype=np.float32) for _ in range(R)]
+    w16 = [np.zeros(S, dtype=np.uint16) for _ in range(R)]
+    oracle.retrieve(acc_h, w32, N, scale=scale, nthreads=THREADS)
+    oracle.retrieve(acc_h, w16, N, scale=scale, nthreads=THREADS)
+    for r in range(R):
+        assert_bits_equal(out32[r].cpu().numpy(), w32[r], f"retrieve f32 rank {r}")
+        assert_bits_equal(out16[r].cpu().numpy().view(np.uint16), w16[r], f"retrieve bf16 rank {r}")
+    L.close()
+
+
 def test_1p5b_layer(oracle):
     w = inputs.workload("1.5b")
     full_layer_case(oracle, w.numel[0], w.R, [(0, 0), (0, 1), (3, 0), (7, 2)], seed=w.seed)

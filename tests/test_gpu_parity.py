@@ -211,3 +211,107 @@ def test_non_default_stream_and_probe_copy():
     odc.probe_copy(dst, src, n * 4, stream=s)
     s.synchronize()
     assert torch.equal(src, dst)
+
+
+# ----------------------------------------------------------------------------- weighted, retrieve
+def weighted_retrieve_case(oracle, numel, R, seed, weights, scale):
+    """reset, weighted contributions in order, then retrieval as binary32 and as bf16."""
+    print(f"weighted/retrieve case R={R} T={len(numel)} total={sum(numel)} weights={weights} scale={scale}", flush=True)
+    case = DeviceCase(R, numel, with_params=False)
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    oracle.reset_batched(acc_host, numel, case.shard_off)
+    for k, w in enumerate(weights):
+        g = inputs.normal_bf16(case.full_n, 1e-2, seed=(seed, 3, k))
+        case.grad.t.copy_(to_dev_u16(g))
+        if w is None:
+            case.layout.scatter_accumulate(case.grad.t, case.acc_ptrs, 0, k)
+            oracle.accumulate_batched(g, acc_host, numel, case.shard_off, case.full_off)
+        else:
+            case.layout.scatter_accumulate_weighted(case.grad.t, case.acc_ptrs, 0, k, w)
+            oracle.accumulate_weighted_batched(g, acc_host, numel, case.shard_off, case.full_off, w)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"weighted accumulate rank {r}")
+    from gpu_util import Guarded, i16
+    for out_dtype, np_dtype, t_dtype, fill in ((odc.ODC_OUT_F32, np.float32, torch.float32, float(PAD32)),
+                                               (odc.ODC_OUT_BF16, np.uint16, torch.int16, i16(PAD16))):
+        outs = [Guarded(case.arena, t_dtype, fill) for _ in range(R)]
+        case.layout.retrieve_grads(case.acc_ptrs, [o.t for o in outs], scale, out_dtype)
+        want = [np.full(case.arena, PAD32 if np_dtype == np.float32 else PAD16, dtype=np_dtype) for _ in range(R)]
+        oracle.retrieve_batched(acc_host, want, numel, case.shard_off, scale=scale)
+        for r in range(R):
+            got = outs[r].t.cpu().numpy()
+            got = got.view(np.uint16) if np_dtype == np.uint16 else got
+            assert_bits_equal(got, want[r], f"retrieve dtype {out_dtype} rank {r}")
+            outs[r].check()
+    for r, a in enumerate(case.acc_host()):            # retrieval leaves the accumulators alone
+        assert_bits_equal(a, acc_host[r], f"accumulator after retrieve rank {r}")
+    case.check_guards()
+    case.close()
+
+
+@pytest.mark.parametrize("numel,R", [([1_048_589], 4), ([1], 64), ([4099], 8), ([3_000_001], 16), ([350], 70),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+                                     ([30000, 17, 2048, 2049, 1_000_001], 5), ([5] * 70 + [100_000], 70)])
+def test_weighted_accumulate_and_retrieve(oracle, numel, R):
+    weighted_retrieve_case(oracle, numel, R, seed=sum(numel) % 997, weights=[0.37, None, -1.5, 1.0 / 3.0],
+                           scale=1.0 / 7.0)
+
+
+def test_weighted_and_retrieve_on_stress_config(oracle):
+    w = inputs.workload("stress")
+    weighted_retrieve_case(oracle, list(w.numel), w.R, seed=w.seed, weights=[0.25, 1.7], scale=0.5)
+
+
+def test_weight_one_equals_unweighted_and_scale_one_is_a_copy(oracle):
+    N, R = 2_000_003, 4
+    case = DeviceCase(R, [N], with_params=False)
+    other = [torch.full((case.arena,), float(PAD32), dtype=torch.float32, device="cuda") for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    case.layout.reset_accum(other)
+    for k in range(3):
+        case.grad.t.copy_(to_dev_u16(inputs.normal_bf16(N, 1e-3, seed=(44, k))))
+        case.layout.scatter_accumulate(case.grad.t, case.acc_ptrs, 1, k)
+        case.layout.scatter_accumulate_weighted(case.grad.t, other, 1, k, 1.0)
+    out = [torch.zeros(case.arena, dtype=torch.float32, device="cuda") for _ in range(R)]
+    case.layout.retrieve_grads(other, out, 1.0, odc.ODC_OUT_F32)
+    for r in range(R):
+        valid = case.layout.valid_elems(0, r)
+        a = case.acc[r].t.cpu().numpy()
+        assert_bits_equal(other[r].cpu().numpy(), a, f"weight 1 rank {r}")
+        assert_bits_equal(out[r].cpu().numpy()[:valid], a[:valid], f"scale 1 rank {r}")
+        assert (out[r].cpu().numpy()[valid:] == 0).all()
+    case.close()
+
+
+def test_weighted_unordered_within_tolerance(oracle):
+    """Unordered weighted contributions: |x - ref64| <= 1e-6 * sum |w g| against a float64 sum."""
+    N, R = 500_009, 8
+    ws = [0.3, 1.0, 2.5, 0.7, 1.1, 0.05, 3.0, 1.9]
+    case = DeviceCase(R, [N], with_params=False)
+    case.layout.reset_accum(case.acc_ptrs)
+    ref = np.zeros(N)
+    mag = np.zeros(N)
+    for k, w in enumerate(ws):
+        g = inputs.normal_bf16(N, 1e-3, seed=(45, k))
+        case.grad.t.copy_(to_dev_u16(g))
+        case.layout.scatter_accumulate_weighted(case.grad.t, case.acc_ptrs, k % R, k, w, odc.ODC_UNORDERED)
+        v = np.float64(np.float32(w)) * inputs.bf16_bits_to_f32(g).astype(np.float64)
+        ref += v
+        mag += np.abs(v)
+    S = case.S[0]
+    got = np.concatenate([a[:S] for a in case.acc_host()])[:N].astype(np.float64)
+    assert (np.abs(got - ref) <= 1e-6 * mag).all()
+    case.close()
+
+
+def test_retrieve_argument_errors():
+    case = DeviceCase(4, [1000], with_params=False)
+    out = [torch.zeros(case.arena, dtype=torch.float32, device="cuda") for _ in range(4)]
+    assert odc.retrieve_grads_rc(case.layout, case.acc_ptrs, out, 1.0, 7) == odc.ODC_ERR_INVALID_ARG
+    assert odc.retrieve_grads_rc(case.layout, case.acc_ptrs, None, 1.0, 0) == odc.ODC_ERR_INVALID_ARG
+    bad = [out[0], out[1][1:], out[2], out[3]]
+    assert odc.retrieve_grads_rc(case.layout, case.acc_ptrs, bad, 1.0, 0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.retrieve_grads_rc(case.layout, case.acc_ptrs, out, 1.0, 0) == 0
+    torch.cuda.synchronize()
+    case.close()

@@ -30,7 +30,7 @@ def test_error_strings_and_codes():
     header = open(os.path.join(ROOT, "include", "odc.h")).read()
     for name in ("ODC_ERR_INVALID_ARG", "ODC_ERR_ALIGNMENT", "ODC_ERR_ORDER", "ODC_ERR_OVERFLOW",
                  "ODC_ERR_HIP", "ODC_ERR_NO_DEVICE", "ODC_ERR_NOMEM", "ODC_MAX_RANKS",
-                 "ODC_LAYOUT_HOST_ONLY", "ODC_ORDERED", "ODC_UNORDERED"):
+                 "ODC_LAYOUT_HOST_ONLY", "ODC_ORDERED", "ODC_UNORDERED", "ODC_OUT_F32", "ODC_OUT_BF16"):
         m = re.search(rf"#define {name} \(?(-?\d+)\)?", header)
         assert m and int(m.group(1)) == getattr(odc, name), name
 
@@ -131,6 +131,17 @@ def test_launch_argument_errors_are_found_before_any_launch():
     assert sa(L, 0x8000, good, 0, 0, 5, 0) == odc.ODC_ERR_INVALID_ARG
     assert sa(L, 0x8004, good, 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_ALIGNMENT
     assert sa(L, 0x8000, [0x1000, 0x2000, 0x3004, 0x4000], 0, 0, odc.ODC_ORDERED, 0) == odc.ODC_ERR_ALIGNMENT
+
+    lib = odc.lib()
+    import ctypes
+    arr = (ctypes.c_void_p * 4)(*good)
+    assert lib.odc_scatter_accumulate_weighted(L.handle, 0x8000, arr, 0, 0, 0.5, odc.ODC_ORDERED, None) == odc.ODC_ERR_NO_DEVICE
+    assert lib.odc_scatter_accumulate_weighted(L.handle, 0x8000, arr, 9, 0, 0.5, odc.ODC_ORDERED, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_scatter_accumulate_weighted(L.handle, 0x8002, arr, 0, 0, 0.5, odc.ODC_ORDERED, None) == odc.ODC_ERR_ALIGNMENT
+    assert odc.retrieve_grads_rc(L, good, good, 1.0, odc.ODC_OUT_F32, 0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.retrieve_grads_rc(L, good, good, 1.0, 5, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.retrieve_grads_rc(L, good, None, 1.0, 0, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.retrieve_grads_rc(L, good, [0x1000, 0x2000, 0x3002, 0x4000], 1.0, 0, 0) == odc.ODC_ERR_ALIGNMENT
 
     assert odc.reset_accum_rc(L, good, 0) == odc.ODC_ERR_NO_DEVICE
     assert odc.reset_accum_rc(L, None, 0) == odc.ODC_ERR_INVALID_ARG

@@ -45,9 +45,9 @@ def placement(numel, R):
     return S, so, fo, so[-1] + S[-1], fo[-1] + numel[-1]
 
 
-def run(emu, d, op, R, threads=256, unroll=4, nt=1, remap=0, atomic=0, cap=0, rg=1):
-    p = subprocess.run([emu, str(d), op, str(R), str(threads), str(unroll), str(nt), str(remap),
-                        str(atomic), str(cap), str(rg)], capture_output=True, text=True,
+def run(emu, d, op, R, **knobs):
+    p = subprocess.run([emu, str(d), op, str(R)] + [f"{k}={v}" for k, v in knobs.items()],
+                       capture_output=True, text=True,
                        env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0"})
     assert p.returncode == 0, p.stderr[-3000:]
 
@@ -118,3 +118,49 @@ def test_emulated_reset_and_accumulate(oracle, emu, tmp_path, numel, R, threads,
         got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
         oracle.accumulate_batched(g, acc, numel, so, fo)
         assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("threads,unroll,nt,atomic,rg,weight", [(64, 1, 1, 0, 4, 0.37), (256, 4, 0, 0, 1, -1.5),
+                                                                (128, 2, 1, 1, 8, 0.5)])
+def test_emulated_weighted_accumulate(oracle, emu, tmp_path, numel, R, threads, unroll, nt, atomic, rg, weight):
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc, numel, so)
+    got = np.concatenate(acc)
+    for k in range(2):
+        g = inputs.normal_bf16(full_n, 1e-2, seed=(3, k))
+        g.tofile(tmp_path / "grad.u16")
+        got.tofile(tmp_path / "acc.f32")
+        run(emu, tmp_path, "accum", R, threads=threads, unroll=unroll, nt=nt, atomic=atomic, rg=rg, weighted=1,
+            weight=repr(float(np.float32(weight))))
+        got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+        if atomic:
+            # the unordered form rounds the product first: power-of-two weight keeps it exact
+            assert weight == 0.5
+        oracle.accumulate_weighted_batched(g, acc, numel, so, fo, weight)
+        assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("threads,unroll,nt,rg,bf16,scale", [(256, 1, 1, 4, 0, 1.0), (64, 4, 0, 1, 1, 0.125),
+                                                             (128, 2, 1, 8, 1, 1.0 / 3.0), (256, 4, 1, 2, 0, 1.0 / 7.0)])
+def test_emulated_retrieve(oracle, emu, tmp_path, numel, R, threads, unroll, nt, rg, bf16, scale):
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    rng = np.random.default_rng(5)
+    acc = [(rng.standard_normal(arena) * 1e-2).astype(np.float32) for _ in range(R)]
+    dtype = np.uint16 if bf16 else np.float32
+    fill = 0xDEAD if bf16 else PAD32
+    out = [np.full(arena, fill, dtype=dtype) for _ in range(R)]
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    np.concatenate(out).tofile(tmp_path / "out.bin")
+    run(emu, tmp_path, "retrieve", R, threads=threads, unroll=unroll, nt=nt, rg=rg, bf16=bf16,
+        scale=repr(float(np.float32(scale))))
+    got = np.fromfile(tmp_path / "out.out", dtype=dtype)
+    oracle.retrieve_batched(acc, out, numel, so, scale=scale)
+    view = np.uint16 if bf16 else np.uint32
+    assert np.array_equal(got.view(view), np.concatenate(out).view(view))
+    assert np.array_equal(np.fromfile(tmp_path / "acc.out", dtype=np.float32).view(np.uint32),
+                          np.concatenate(acc).view(np.uint32))          # accumulators untouched
