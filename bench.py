@@ -254,6 +254,12 @@ def main():
     gat_med, gat_min = time_kernel(lambda: L.gather(s0[0], full), torch)
     rst_med, rst_min = time_kernel(lambda: L.reset_accum(s0[1]), torch)
     wac_med, wac_min = time_kernel(lambda: _accum_once(L, pool[1], s0[1], odc, weight=0.37), torch)
+    fused = {}
+    for K in (2, 4, 8):
+        if K <= len(pool):
+            f_med, _ = time_kernel(lambda: _accum_fused(L, pool[:K], s0[1], odc), torch, reps=10)
+            fused[f"x{K}"] = {"actual_GBs": round((2 * K + 8) * total / f_med / 1e6, 1),
+                              "effective_GBs_10B_rule": round(10 * K * total / f_med / 1e6, 1)}
     arena = L.rank_arena_elems()
     out32 = [torch.empty(arena, dtype=torch.float32, device="cuda") for _ in range(w.R)]
     r32_med, r32_min = time_kernel(lambda: L.retrieve_grads(s0[1], out32, 0.125, odc.ODC_OUT_F32), torch)
@@ -296,6 +302,7 @@ def main():
             "gather_GBs": {"median": round(4 * total / gat_med / 1e6, 1), "best": round(4 * total / gat_min / 1e6, 1)},
             "reset_GBs": {"median": round(4 * total / rst_med / 1e6, 1), "best": round(4 * total / rst_min / 1e6, 1)},
             "scatter_accumulate_weighted_GBs": {"median": round(10 * total / wac_med / 1e6, 1), "best": round(10 * total / wac_min / 1e6, 1)},
+            "scatter_accumulate_fused (K contributions per pass, (2K+8) B/elem actual)": fused,
             "retrieve_f32_GBs": {"median": round(8 * total / r32_med / 1e6, 1), "best": round(8 * total / r32_min / 1e6, 1)},
             "retrieve_bf16_GBs": {"median": round(6 * total / r16_med / 1e6, 1), "best": round(6 * total / r16_min / 1e6, 1)},
             "plain_copy_GBs": {"median": round(2 * nbytes_copy / cp_med / 1e6, 1), "best": round(2 * nbytes_copy / cp_min / 1e6, 1)},
@@ -319,6 +326,13 @@ def _accum_once(L, g, acc, odc, weight=None):
         L.scatter_accumulate(g, acc, 0, _seq[0], odc.ODC_ORDERED)
     else:
         L.scatter_accumulate_weighted(g, acc, 0, _seq[0], weight, odc.ODC_ORDERED)
+
+
+def _accum_fused(L, grads, acc, odc):
+    k = len(grads)
+    ms = list(range(_seq[0] + 1, _seq[0] + 1 + k))
+    _seq[0] += k
+    L.scatter_accumulate_multi(grads, acc, [0] * k, ms, odc.ODC_ORDERED)
 
 
 if __name__ == "__main__":

@@ -141,6 +141,26 @@ int odc_scatter_accumulate_weighted(const odc_layout_t *layout, const void *grad
                                     void *const *accum_shards, int worker, int microbatch,
                                     float weight, int flags, void *stream);
 
+/*
+ * Fused form of odc_scatter_accumulate for an owner that finds several contributions staged
+ * at once (Appendix B gives every client its own receive buffer, so up to one contribution
+ * per client can be waiting): `count` gradients are applied in the given order in ONE pass,
+ *   acc = (((acc + g_0) + g_1) + ... + g_{count-1})
+ * the same left-to-right binary32 sequence that `count` single calls perform, so in
+ * ODC_ORDERED mode the result is bit-identical to theirs, while the accumulators are read
+ * and written once: (2*count + 8) bytes per valid element instead of 10*count.
+ *   count         1 .. ODC_MAX_FUSED
+ *   grads         [count] host array of device pointers (bf16, full layout, 16-byte aligned)
+ *   workers, microbatches  [count] host arrays; in ODC_ORDERED mode strictly ascending
+ *                 (worker, microbatch) pairs, the first one after this accumulator set's history
+ *                 (ODC_ERR_ORDER otherwise, nothing enqueued); the history becomes the last pair.
+ *   ODC_UNORDERED sums the count values in registers and issues one atomic add per element.
+ */
+#define ODC_MAX_FUSED 8
+int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const void *const *grads,
+                                 void *const *accum_shards, const int *workers, const int *microbatches,
+                                 int flags, void *stream);
+
 /* odc_retrieve_grads output types */
 #define ODC_OUT_F32 0
 #define ODC_OUT_BF16 1

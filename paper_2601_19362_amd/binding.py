@@ -24,6 +24,7 @@ ODC_MAX_RANKS = 4096
 ODC_LAYOUT_HOST_ONLY = 1
 ODC_ORDERED = 0
 ODC_UNORDERED = 1
+ODC_MAX_FUSED = 8
 ODC_OUT_F32 = 0
 ODC_OUT_BF16 = 1
 
@@ -31,7 +32,7 @@ EXPORTS = (
     "odc_init_layout", "odc_free_layout", "odc_num_ranks", "odc_num_tensors", "odc_numel",
     "odc_shard_elems", "odc_valid_elems", "odc_rank_arena_elems", "odc_full_elems",
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
-    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_retrieve_grads", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
 _i64 = ctypes.c_int64
@@ -85,6 +86,9 @@ def lib():
         L.odc_scatter_accumulate_weighted.restype = _int
         L.odc_scatter_accumulate_weighted.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _int, _int, ctypes.c_float,
                                                       _int, _vp]
+        L.odc_scatter_accumulate_multi.restype = _int
+        L.odc_scatter_accumulate_multi.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
+                                                   ctypes.POINTER(_int), ctypes.POINTER(_int), _int, _vp]
         L.odc_retrieve_grads.restype = _int
         L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
@@ -225,6 +229,12 @@ class Layout:
         if rc != ODC_OK:
             raise OdcError(rc, "odc_scatter_accumulate_weighted")
 
+    def scatter_accumulate_multi(self, grads, accum_shards, workers, microbatches, flags: int = ODC_ORDERED,
+                                 stream=None) -> None:
+        rc = scatter_accumulate_multi_rc(self, grads, accum_shards, workers, microbatches, flags, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_scatter_accumulate_multi")
+
     def retrieve_grads(self, accum_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
                        stream=None) -> None:
         rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
@@ -248,6 +258,16 @@ def scatter_accumulate_rc(layout: Layout, grad_full, accum_shards, worker: int, 
     return lib().odc_scatter_accumulate(layout.handle, _ptr(grad_full),
                                         _ptr_array(accum_shards, layout.R), int(worker),
                                         int(microbatch), int(flags), _stream(stream))
+
+
+def scatter_accumulate_multi_rc(layout: Layout, grads, accum_shards, workers, microbatches,
+                                flags: int = ODC_ORDERED, stream=None) -> int:
+    k = len(grads)
+    garr = (_vp * max(k, 1))(*[_ptr(g) for g in grads])
+    warr = (_int * max(k, 1))(*[int(w) for w in workers])
+    marr = (_int * max(k, 1))(*[int(m) for m in microbatches])
+    return lib().odc_scatter_accumulate_multi(layout.handle, k, garr, _ptr_array(accum_shards, layout.R), warr,
+                                              marr, int(flags), _stream(stream))
 
 
 def retrieve_grads_rc(layout: Layout, accum_shards, out_shards, scale: float = 1.0,

@@ -234,6 +234,69 @@ int odc_scatter_accumulate_weighted(const odc_layout_t *L, const void *grad_full
     return scatter_accumulate_impl(L, grad_full, accum_shards, worker, microbatch, true, weight, flags, stream);
 }
 
+int odc_scatter_accumulate_multi(const odc_layout_t *L, int count, const void *const *grads,
+                                 void *const *accum_shards, const int *workers, const int *microbatches,
+                                 int flags, void *stream)
+{
+    int rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (!grads || !workers || !microbatches || count < 1 || count > ODC_MAX_FUSED) return ODC_ERR_INVALID_ARG;
+    if (flags != ODC_ORDERED && flags != ODC_UNORDERED) return ODC_ERR_INVALID_ARG;
+    for (int k = 0; k < count; ++k) {
+        if (!grads[k] || workers[k] < 0 || workers[k] >= L->host.R || microbatches[k] < 0)
+            return ODC_ERR_INVALID_ARG;
+    }
+    for (int k = 0; k < count; ++k)
+        if (!aligned16(grads[k])) return ODC_ERR_ALIGNMENT;
+    if (count == 1)
+        return scatter_accumulate_impl(L, grads[0], accum_shards, workers[0], microbatches[0], false, 1.0f, flags,
+                                       stream);
+
+    const bool atomic = flags == ODC_UNORDERED;
+    odc_layout_t *M = const_cast<odc_layout_t *>(L);
+    std::unique_lock<std::mutex> lock(M->mu, std::defer_lock);
+    std::pair<int, int> *slot = nullptr;
+    bool inserted = false;
+    const std::pair<int, int> last_now{workers[count - 1], microbatches[count - 1]};
+    if (!atomic) {
+        // ascending inside the call, and the first one after the history of this accumulator set
+        for (int k = 1; k < count; ++k) {
+            const std::pair<int, int> a{workers[k - 1], microbatches[k - 1]}, b{workers[k], microbatches[k]};
+            if (!(a < b)) return ODC_ERR_ORDER;
+        }
+        lock.lock();
+        try {
+            auto res = M->last.try_emplace(accum_shards[0], -1, -1);
+            slot = &res.first->second;
+            inserted = res.second;
+        } catch (...) {
+            return ODC_ERR_NOMEM;
+        }
+        if (!(*slot < std::pair<int, int>{workers[0], microbatches[0]})) {
+            if (inserted) M->last.erase(accum_shards[0]);
+            return ODC_ERR_ORDER;
+        }
+    }
+    rc = check_device(L);
+    const odc::HostLayout &H = L->host;
+    for (int r0 = 0; rc == ODC_OK && r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_accum_multi_flat(accum_shards + r0, r0, nr, grads, count, H.desc[0].S, H.desc[0].numel,
+                                             atomic, stream);
+        else
+            e = odc::launch_accum_multi_batched(L->table, accum_shards + r0, r0, nr, grads, count, atomic, stream);
+        if (e != 0) rc = hip_fail(static_cast<hipError_t>(e));
+        else if (slot) {
+            *slot = last_now;
+            inserted = false;
+        }
+    }
+    if (inserted) M->last.erase(accum_shards[0]);
+    return rc;
+}
+
 int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, void *const *out_shards,
                        float scale, int out_dtype, void *stream)
 {

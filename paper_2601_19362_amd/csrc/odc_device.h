@@ -794,6 +794,111 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
     }
 }
 
+// ---------------------------------------------------------------------------- fused accumulate
+// K contributions applied in one pass (an owner draining K staged client buffers at once,
+// paper Appendix B): acc = (((acc + g_1) + g_2) + ... + g_K), the same left-to-right binary32
+// sequence, starting from the stored accumulator value, that K single calls would perform, so
+// the ordered result is bit-identical -- but the accumulator is read and written once:
+// (2K + 8) bytes per element instead of 10K.  Fixed launch shape: one wavefront per
+// workgroup, one accumulator vector per lane, non-temporal accesses.  The unordered form sums
+// the K values in registers and issues one atomic add per element.
+
+constexpr int kMaxFused = 8;
+
+struct GradPtrs {
+    const uint16_t *p[kMaxFused];
+};
+
+template <int K, bool ATOMIC>
+__device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q)
+{
+    u32x2 gv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) gv[k] = ld_u64_unaligned<true>(grads.p[k] + goff + 4 * q);
+    f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
+    if constexpr (ATOMIC) {
+        f32x4 sum = {widen_lo(gv[0].x), widen_hi(gv[0].x), widen_lo(gv[0].y), widen_hi(gv[0].y)};
+#pragma unroll
+        for (int k = 1; k < K; ++k) sum = add4<false>(sum, gv[k], 1.0f);
+        unsafeAtomicAdd(acc + 4 * q + 0, sum.x);
+        unsafeAtomicAdd(acc + 4 * q + 1, sum.y);
+        unsafeAtomicAdd(acc + 4 * q + 2, sum.z);
+        unsafeAtomicAdd(acc + 4 * q + 3, sum.w);
+    } else {
+        f32x4 a = ld<true>(av);
+#pragma unroll
+        for (int k = 0; k < K; ++k) a = add4<false>(a, gv[k], 1.0f);
+        st<true>(av, a);
+    }
+}
+
+template <int K, bool ATOMIC>
+__device__ __forceinline__ void accum_multi_one(float *acc, const GradPtrs &grads, int64_t goff, int64_t e)
+{
+    if constexpr (ATOMIC) {
+        float sum = widen_one(ld_u16(grads.p[0] + goff + e));
+#pragma unroll
+        for (int k = 1; k < K; ++k) sum = sum + widen_one(ld_u16(grads.p[k] + goff + e));
+        unsafeAtomicAdd(acc + e, sum);
+    } else {
+        float a = ld_f32(acc + e);
+#pragma unroll
+        for (int k = 0; k < K; ++k) a = a + widen_one(ld_u16(grads.p[k] + goff + e));
+        st_f32(acc + e, a);
+    }
+}
+
+template <int K, bool ATOMIC>
+__global__ __launch_bounds__(64) void k_accum_multi_flat(RankPtrs accs, GradPtrs grads, int64_t S, int64_t N, int r0)
+{
+    const int64_t base = static_cast<int64_t>(r0 + static_cast<int>(blockIdx.y)) * S;
+    int64_t valid = N - base;
+    if (valid > S) valid = S;
+    if (valid <= 0) return;
+    float *__restrict__ acc = static_cast<float *>(accs.p[blockIdx.y]);
+    const int64_t nitem = valid >> 2;
+    const int tail = static_cast<int>(valid & 3);
+    const int64_t ntiles = (nitem + 63) >> 6;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t q = (tile << 6) + threadIdx.x;
+        if (q < nitem) accum_multi_vec<K, ATOMIC>(acc, grads, base, q);
+    }
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail)
+        accum_multi_one<K, ATOMIC>(acc, grads, base, 4 * nitem + threadIdx.x);
+}
+
+// Batched form: one workgroup per (tile of the rank arena, owner), owner fastest.
+template <int K, bool ATOMIC>
+__global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTable tb, RankPtrs accs, GradPtrs grads,
+                                                                       int r0, int nr)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t nwork = ntiles * nr;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / nr;
+        const int rl = static_cast<int>(work - tile * nr);
+        float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = (tile << kChunkShift) + a_rel;
+            if (a >= tb.arena_elems) continue;
+            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const int64_t slot = a - d.shard_off;
+            const int cnt = valid_from(d, r0 + rl, slot, 4);
+            // gradient element that pairs with arena element a: goff + a
+            const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
+            if (cnt == 4) accum_multi_vec<K, ATOMIC>(arena, grads, goff, a >> 2);
+            else
+                for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
+        }
+    }
+}
+
 // -------------------------------------------------------------------------------- retrieve
 // Minibatch-end retrieval (paper Section 3.2): each owner's accumulated gradient shard is
 // read, multiplied by `scale` (one binary32 multiply) and written to the owner's output shard

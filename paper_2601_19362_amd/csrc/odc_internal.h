@@ -107,6 +107,11 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
 constexpr int kMaxTensorsPerChunk = (1 << kChunkShift) / static_cast<int>(kAlignElems);
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr,
                          const void *grad, bool atomic, bool weighted, float w, void *stream);
+// Fused form: `count` (2..8) gradients applied in order in one pass.
+int launch_accum_multi_flat(void *const *ptrs, int r0, int nr, const void *const *grads, int count, int64_t S,
+                            int64_t N, bool atomic, void *stream);
+int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *const *grads,
+                               int count, bool atomic, void *stream);
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream);
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,

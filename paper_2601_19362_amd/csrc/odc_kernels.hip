@@ -178,6 +178,53 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     return finish();
 }
 
+#define ODC_DISPATCH_K(KV, CALL)                                \
+    do {                                                        \
+        switch (KV) {                                           \
+            case 2: { constexpr int K_ = 2; CALL; } break;       \
+            case 3: { constexpr int K_ = 3; CALL; } break;       \
+            case 4: { constexpr int K_ = 4; CALL; } break;       \
+            case 5: { constexpr int K_ = 5; CALL; } break;       \
+            case 6: { constexpr int K_ = 6; CALL; } break;       \
+            case 7: { constexpr int K_ = 7; CALL; } break;       \
+            default: { constexpr int K_ = 8; CALL; } break;      \
+        }                                                       \
+    } while (0)
+
+static GradPtrs pack_grads(const void *const *grads, int count)
+{
+    GradPtrs gp;
+    for (int k = 0; k < kMaxFused; ++k) gp.p[k] = static_cast<const uint16_t *>(k < count ? grads[k] : grads[0]);
+    return gp;
+}
+
+int launch_accum_multi_flat(void *const *ptrs, int r0, int nr, const void *const *grads, int count, int64_t S,
+                            int64_t N, bool atomic, void *stream)
+{
+    const RankPtrs rp = pack(ptrs, nr);
+    const GradPtrs gp = pack_grads(grads, count);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid = plain_grid((S >> 2) + 1, 64, nr);
+    if (atomic) ODC_DISPATCH_K(count, (k_accum_multi_flat<K_, true><<<grid, 64, 0, s>>>(rp, gp, S, N, r0)));
+    else ODC_DISPATCH_K(count, (k_accum_multi_flat<K_, false><<<grid, 64, 0, s>>>(rp, gp, S, N, r0)));
+    return finish();
+}
+
+int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *const *grads,
+                               int count, bool atomic, void *stream)
+{
+    const RankPtrs rp = pack(ptrs, nr);
+    const GradPtrs gp = pack_grads(grads, count);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+    const dim3 grid(batched_grid_x(work));
+    if (atomic)
+        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, true><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0, nr)));
+    else
+        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, false><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0, nr)));
+    return finish();
+}
+
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream)
 {

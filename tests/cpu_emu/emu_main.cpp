@@ -141,7 +141,7 @@ int main(int argc, char **argv)
     }
     const std::string dir = argv[1], op = argv[2];
     const int R = std::atoi(argv[3]);
-    int threads = 256, unroll = 4, nt = 1, remap = 0, atomic = 0, cap = 0, rg = 1, weighted = 0, bf16 = 0;
+    int threads = 256, unroll = 4, nt = 1, remap = 0, atomic = 0, cap = 0, rg = 1, weighted = 0, bf16 = 0, count = 2;
     float weight = 1.0f, scale = 1.0f;
     for (int k = 4; k < argc; ++k) {
         const std::string kv = argv[k];
@@ -157,6 +157,7 @@ int main(int argc, char **argv)
         else if (key == "rg") rg = std::atoi(val.c_str());
         else if (key == "weighted") weighted = std::atoi(val.c_str());
         else if (key == "bf16") bf16 = std::atoi(val.c_str());
+        else if (key == "count") count = std::atoi(val.c_str());
         else if (key == "weight") weight = std::strtof(val.c_str(), nullptr);
         else if (key == "scale") scale = std::strtof(val.c_str(), nullptr);
         else {
@@ -272,6 +273,63 @@ int main(int argc, char **argv)
         std::free(grad);
         return 0;
     }
+    if (op == "accum_multi") {
+        if (count < 2 || count > kMaxFused) return 2;
+        std::vector<float> all = read_file<float>(dir + "/acc.f32");
+        if (all.size() != arena * static_cast<size_t>(R)) return 4;
+        GradPtrs gp{};
+        std::vector<uint16_t *> gbufs;
+        for (int k = 0; k < count; ++k) {
+            std::vector<uint16_t> gi = read_file<uint16_t>(dir + "/grad" + std::to_string(k) + ".u16");
+            if (gi.size() != full_n) return 4;
+            uint16_t *g = static_cast<uint16_t *>(std::malloc(full_n * 2));
+            std::memcpy(g, gi.data(), full_n * 2);
+            gbufs.push_back(g);
+        }
+        for (int k = 0; k < kMaxFused; ++k) gp.p[k] = gbufs[k < count ? k : 0];
+        std::vector<float *> bufs(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            bufs[r] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(bufs[r], all.data() + arena * r, arena * 4);
+        }
+#define EMU_K(CALL)                                            \
+    do {                                                       \
+        switch (count) {                                       \
+            case 2: { constexpr int K_ = 2; CALL; } break;      \
+            case 3: { constexpr int K_ = 3; CALL; } break;      \
+            case 4: { constexpr int K_ = 4; CALL; } break;      \
+            case 5: { constexpr int K_ = 5; CALL; } break;      \
+            case 6: { constexpr int K_ = 6; CALL; } break;      \
+            case 7: { constexpr int K_ = 7; CALL; } break;      \
+            default: { constexpr int K_ = 8; CALL; } break;     \
+        }                                                      \
+    } while (0)
+        for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+            const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+            RankPtrs rp{};
+            for (int k = 0; k < nr; ++k) rp.p[k] = bufs[r0 + k];
+            if (flat) {
+                const unsigned gx = grid_x_for((S >> 2) + 1, 64, cap);
+                if (atomic) EMU_K(run_grid(64, gx, nr, [&] { k_accum_multi_flat<K_, true>(rp, gp, S, N, r0); }));
+                else EMU_K(run_grid(64, gx, nr, [&] { k_accum_multi_flat<K_, false>(rp, gp, S, N, r0); }));
+            } else {
+                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+                const unsigned gx = grid_x_for(work, 1, cap);
+                if (atomic)
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, [&] { k_accum_multi_batched<K_, true>(tb, rp, gp, r0, nr); }));
+                else
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, [&] { k_accum_multi_batched<K_, false>(tb, rp, gp, r0, nr); }));
+            }
+        }
+#undef EMU_K
+        std::vector<float> out(arena * static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) std::memcpy(out.data() + arena * r, bufs[r], arena * 4);
+        write_file(dir + "/acc.out", out.data(), out.size());
+        for (auto *b : bufs) std::free(b);
+        for (auto *g : gbufs) std::free(g);
+        return 0;
+    }
+
     if (op == "retrieve") {
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;

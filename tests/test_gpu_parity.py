@@ -315,3 +315,64 @@ def test_retrieve_argument_errors():
     assert odc.retrieve_grads_rc(case.layout, case.acc_ptrs, out, 1.0, 0) == 0
     torch.cuda.synchronize()
     case.close()
+
+
+# ----------------------------------------------------------------------------- fused contributions
+@pytest.mark.parametrize("numel,R", [([1_048_589], 4), ([4099], 8), ([3_000_001], 16), ([350], 70),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+                                     ([30000, 17, 2048, 2049, 1_000_001], 5)])
+@pytest.mark.parametrize("count", [2, 3, 8])
+def test_fused_contributions_equal_single_calls(oracle, numel, R, count):
+    case = DeviceCase(R, numel, with_params=False)
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    oracle.reset_batched(acc_host, numel, case.shard_off)
+    g0 = inputs.normal_bf16(case.full_n, 1e-2, seed=(80, 0))
+    case.grad.t.copy_(to_dev_u16(g0))
+    case.layout.scatter_accumulate(case.grad.t, case.acc_ptrs, 0, 0)
+    oracle.accumulate_batched(g0, acc_host, numel, case.shard_off, case.full_off)
+    gs = [inputs.normal_bf16(case.full_n, 1e-2, seed=(80, 1 + k)) for k in range(count)]
+    dev = [to_dev_u16(g) for g in gs]
+    case.layout.scatter_accumulate_multi(dev, case.acc_ptrs, [0] * count, list(range(1, count + 1)))
+    for g in gs:
+        oracle.accumulate_batched(g, acc_host, numel, case.shard_off, case.full_off)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"fused x{count} rank {r}")
+    case.check_guards()
+    case.close()
+
+
+def test_fused_order_rules_and_unordered():
+    N, R = 100_003, 4
+    case = DeviceCase(R, [N], with_params=False)
+    L = case.layout
+    L.reset_accum(case.acc_ptrs)
+    gs = [to_dev_u16(inputs.normal_bf16(N, 1e-3, seed=(81, k))) for k in range(3)]
+    rc = lambda w, m, flags=odc.ODC_ORDERED, g=gs: odc.scatter_accumulate_multi_rc(L, g, case.acc_ptrs, w, m, flags)
+    assert rc([0, 0, 1], [0, 1, 0]) == 0
+    assert rc([1, 1, 1], [0, 1, 2]) == odc.ODC_ERR_ORDER         # first pair not after the history (1, 0)
+    assert rc([1, 1, 1], [1, 3, 2]) == odc.ODC_ERR_ORDER         # not ascending inside the call
+    assert rc([1, 2, 3], [1, 0, 0]) == 0
+    assert odc.scatter_accumulate_multi_rc(L, gs + gs + gs, case.acc_ptrs, [3] * 9, list(range(1, 10))) == odc.ODC_ERR_INVALID_ARG
+    assert odc.scatter_accumulate_multi_rc(L, [], case.acc_ptrs, [], []) == odc.ODC_ERR_INVALID_ARG
+    assert rc([9, 9, 9], [0, 1, 2]) == odc.ODC_ERR_INVALID_ARG   # worker out of range
+    assert odc.scatter_accumulate_multi_rc(L, gs[:1], case.acc_ptrs, [3], [5]) == 0   # count 1 = the single call
+    assert rc([0, 0, 0], [0, 0, 0], odc.ODC_UNORDERED) == 0      # unordered: no order rules
+    torch.cuda.synchronize()
+    case.close()
+
+
+def test_fused_unordered_within_tolerance(oracle):
+    N, R = 500_009, 8
+    case = DeviceCase(R, [N], with_params=False)
+    case.layout.reset_accum(case.acc_ptrs)
+    gs = [inputs.normal_bf16(N, 1e-3, seed=(82, k)) for k in range(8)]
+    dev = [to_dev_u16(g) for g in gs]
+    case.layout.scatter_accumulate_multi(dev[:5], case.acc_ptrs, [0] * 5, [0] * 5, odc.ODC_UNORDERED)
+    case.layout.scatter_accumulate_multi(dev[5:], case.acc_ptrs, [0] * 3, [0] * 3, odc.ODC_UNORDERED)
+    ref = sum(inputs.bf16_bits_to_f32(g).astype(np.float64) for g in gs)
+    mag = sum(np.abs(inputs.bf16_bits_to_f32(g).astype(np.float64)) for g in gs)
+    S = case.S[0]
+    got = np.concatenate([a[:S] for a in case.acc_host()])[:N].astype(np.float64)
+    assert (np.abs(got - ref) <= 1e-6 * mag).all()
+    case.close()

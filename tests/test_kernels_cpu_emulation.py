@@ -164,3 +164,22 @@ def test_emulated_retrieve(oracle, emu, tmp_path, numel, R, threads, unroll, nt,
     assert np.array_equal(got.view(view), np.concatenate(out).view(view))
     assert np.array_equal(np.fromfile(tmp_path / "acc.out", dtype=np.float32).view(np.uint32),
                           np.concatenate(acc).view(np.uint32))          # accumulators untouched
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("count,cap", [(2, 0), (5, 3), (8, 0)])
+def test_emulated_fused_accumulate(oracle, emu, tmp_path, numel, R, count, cap):
+    """K contributions in one pass equal K single ordered contributions bit for bit."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc, numel, so)
+    oracle.accumulate_batched(inputs.normal_bf16(full_n, 1e-2, seed=70), acc, numel, so, fo)  # non-zero start
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    for k in range(count):
+        g = inputs.normal_bf16(full_n, 1e-2, seed=(71, k))
+        g.tofile(tmp_path / f"grad{k}.u16")
+        oracle.accumulate_batched(g, acc, numel, so, fo)
+    run(emu, tmp_path, "accum_multi", R, count=count, cap=cap)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
