@@ -37,6 +37,10 @@ def parse_args():
                     help="do not bracket accumulate launches with events (roofline from a separate pass)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU-baseline sample time")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE")
+    ap.add_argument("--microbatch-plan", default="config", choices=["config", "lb-mini", "lb-micro"],
+                    help="config: the workload's own per-rank microbatch counts; lb-mini / lb-micro: draw a "
+                         "global minibatch of 16 samples per rank from the long-tailed length law and plan it "
+                         "with the library's Karmarkar-Karp packing (paper Section 4)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per accumulate launch (from rocprofv3 --pmc runs); "
                          "default: the figure recorded in profiles/ for the 7b workload")
@@ -226,6 +230,23 @@ def main():
     w = inputs.workload(args.workload)
     layers = args.layers if args.layers > 0 else w.layers
     M = inputs.microbatch_counts(w)
+    plan_info = None
+    if args.microbatch_plan != "config":
+        import numpy as np
+
+        from paper_2601_19362_amd import packing
+
+        rng = np.random.Generator(np.random.Philox(key=1000 + w.seed))
+        seq = [int(v) for v in np.clip(np.rint(np.exp(7.0 + rng.standard_normal(16 * w.R))), 128, 32768)]
+        mode = packing.LB_MINI if args.microbatch_plan == "lb-mini" else packing.LB_MICRO
+        t_plan = time.perf_counter()
+        plan, M = packing.plan_minibatch(seq, w.R, 16384, 0, mode)
+        t_plan = time.perf_counter() - t_plan
+        tc, to, _, bc, bo = packing.plan_runtime(seq, plan, 0)
+        plan_info = {"plan": args.microbatch_plan, "samples": len(seq), "max_tokens": 16384,
+                     "planning_ms": round(t_plan * 1e3, 3), "bubble_rate_collective": round(bc, 4),
+                     "bubble_rate_odc": round(bo, 4)}
+        M = [max(1, m) for m in M]
     total = w.total_numel
     L, sets, full, pool = build_state(w, layers, torch, odc, inputs)
     torch.cuda.synchronize()
@@ -286,7 +307,7 @@ def main():
             "calls_per_step": {"gather": n_g // args.steps, "scatter_accumulate": n_c // args.steps,
                                "reset": n_r // args.steps},
             "bytes_rule": "4 B/elem/gather, 10 B/elem/contribution, 4 B/elem/reset",
-            "tune": args.tune,
+            "tune": args.tune, "microbatch_plan": plan_info or "config",
         },
         "roofline": {
             "bound": "hbm", "kernel": "scatter_accumulate (ordered)",

@@ -14,7 +14,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libodc.so")
-SOURCES = ["odc_layout.cpp", "odc_api.cpp", "odc_kernels.hip"]
+SOURCES = ["odc_layout.cpp", "odc_api.cpp", "odc_packing.cpp", "odc_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-gpu-flush-denormals-to-zero", "-ffp-contract=off", "-fno-fast-math",
