@@ -10,7 +10,8 @@
  * microbatch_partition.  The bodies the paper does not print are fixed as follows:
  *   cost(s)    = s * (s + 6 * hidden)      (Section 4: runtime O(s^2), memory O(s); hidden = 0
  *                                           is the pure quadratic model)
- *   check_oom  = a microbatch is infeasible when its tokens exceed max_tokens
+ *   check_oom  = a microbatch is infeasible when it holds more than one sample and its tokens
+ *                exceed max_tokens (a single longer sample cannot be split and is accepted alone)
  *   ties       = larger spread first, then the partial solution created earlier; inside a
  *                partial solution subsets are ordered by sum (descending), then by smallest index.
  * Everything here is plain host code: pointers are HOST pointers, nothing touches the GPU.
@@ -47,7 +48,7 @@ int odc_kk_partition(const int64_t *costs, int n, int k, int equal_size, int *pa
  *   device_of [n] out, micro_of [n] out: device and microbatch (index within the device) of
  *            every sample; micro_count [world] out: microbatches per device (empty ones are
  *            not counted in LB-Mini; LB-Micro counts the common k on every device).
- * A sample longer than max_tokens ends up alone in a microbatch.
+ * A sample longer than max_tokens is accepted once it is alone in a microbatch.
  */
 int odc_plan_minibatch(const int64_t *seqlens, int n, int world, int64_t max_tokens, int64_t hidden,
                        int mode, int *device_of, int *micro_of, int *micro_count);

@@ -24,8 +24,9 @@ get_compute_costs and check_oom are not printed; the readings taken here:
   * get_compute_costs: cost(s) = s * (s + 6 * hidden) -- the attention term grows with s^2 and
     the dense term with s (Section 4: runtime O(s^2), activation memory O(s)); hidden = 0
     gives the pure quadratic model.  parity unpinned (the paper prints no body).
-  * check_oom: a microbatch is infeasible when its token count exceeds `max_tokens`.
-    parity unpinned.
+  * check_oom: a microbatch is infeasible when it holds more than one sample and its token
+    count exceeds `max_tokens` (a single sample longer than the cap cannot be split, so it is
+    accepted alone).  parity unpinned.
 
 All arithmetic is exact Python integer arithmetic.
 """
@@ -96,13 +97,13 @@ def _micro_parts(seqlens: Sequence[int], k: int, hidden: int) -> List[List[int]]
 
 
 def _oom(seqlens: Sequence[int], parts: List[List[int]], max_tokens: int) -> bool:
-    return any(sum(seqlens[i] for i in p) > max_tokens for p in parts)
+    return any(len(p) > 1 and sum(seqlens[i] for i in p) > max_tokens for p in parts)
 
 
 def microbatch_partition(seqlens: Sequence[int], max_tokens: int, hidden: int = 0, k_start: int = 1) -> List[List[int]]:
-    """One device, LB-Mini: raise k until every microbatch fits.  Empty microbatches are kept
-    out of the result.  A single sample longer than max_tokens can never fit: it is given a
-    microbatch of its own once k reaches the number of samples."""
+    """One device, LB-Mini: raise k until every microbatch fits (a sample longer than
+    max_tokens counts as fitting when it is alone).  Empty microbatches are kept out of the
+    result."""
     n = len(seqlens)
     if n == 0:
         return []

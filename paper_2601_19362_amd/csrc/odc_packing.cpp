@@ -146,7 +146,7 @@ int micro_parts(const int64_t *seqlens, const std::vector<int> &ids, int k, int6
     for (const Subset &s : *parts) {
         int64_t tokens = 0;
         for (int j : s.items) tokens += seqlens[ids[static_cast<size_t>(j)]];
-        if (tokens > max_tokens) *oom = true;
+        if (tokens > max_tokens && s.items.size() > 1) *oom = true;  // a lone oversize sample is accepted
     }
     return ODC_OK;
 }
