@@ -161,6 +161,49 @@ int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const vo
                                  void *const *accum_shards, const int *workers, const int *microbatches,
                                  int flags, void *stream);
 
+/*
+ * Server-side staging (Appendix B).  Every owner keeps one receive buffer per client -- M/N
+ * elements each, M per owner, where M is the layer size and N the number of devices -- because
+ * several clients may push at once while one client's requests are serialised.  A push writes
+ * the worker's slice into its slot of every owner's buffer and then signals the owner; the
+ * owner's daemon accumulates whatever has arrived.  Here the signal is a device-side flag and
+ * the daemon's polling loop becomes odc_stage_drain, which handles what is there and returns
+ * (no kernel ever waits).
+ *
+ *   staging_shards [R] host array of device pointers: owner r's buffer, bf16, R slots of
+ *                  odc_stage_slot_elems() elements (client w's slot starts at w * slot and
+ *                  mirrors the rank arena); 16-byte aligned
+ *   flags          device int32[odc_stage_flag_count()] = R*R flags (owner-major: flag of owner r,
+ *                  client w at r*R + w; 0 empty, 1 full) + 1 counter of refused pushes
+ *   snapshot       device int32[odc_stage_snapshot_count()], scratch owned by the caller; a
+ *                  drain writes and reads it, so two drains that overlap must not share one
+ *
+ * odc_stage_init   zeroes flags (a small fill kernel on `stream`).
+ * odc_stage_push   copies slice r of grad_full (full layout) into slot `worker` of owner r, for
+ *                  every owner whose flag (r, worker) is 0, then raises those flags.  An owner
+ *                  whose slot is still full is skipped and counted in flags[R*R]: a client has
+ *                  one buffer per owner, so it must not push again before the owner has drained.
+ *                  4 bytes per valid element.
+ * odc_stage_drain  takes one snapshot of the flags; every owner with full slots reads and
+ *                  writes its accumulator once and adds the staged slices in ascending client
+ *                  order, acc = (((acc + s_w1) + s_w2) + ...), one binary32 add each -- the
+ *                  same bits as single ordered contributions in that order; then lowers the
+ *                  flags of the snapshot.  Owners with nothing staged are not touched.
+ *                  (2k + 8) bytes per valid element for k staged slices.
+ * All three enqueue on `stream` and return.  Pushes and drains on one stream are ordered by
+ * it; a push running concurrently with a drain on another stream is either wholly inside
+ * that drain's snapshot or left for the next drain.  The ordered-mode history of
+ * odc_scatter_accumulate is not involved: the order is the drain order.
+ */
+int64_t odc_stage_slot_elems(const odc_layout_t *layout);
+int64_t odc_stage_flag_count(const odc_layout_t *layout);
+int64_t odc_stage_snapshot_count(const odc_layout_t *layout);
+int odc_stage_init(const odc_layout_t *layout, void *flags, void *stream);
+int odc_stage_push(const odc_layout_t *layout, const void *grad_full, void *const *staging_shards,
+                   void *flags, int worker, void *stream);
+int odc_stage_drain(const odc_layout_t *layout, const void *const *staging_shards, void *flags,
+                    void *snapshot, void *const *accum_shards, void *stream);
+
 /* odc_retrieve_grads output types */
 #define ODC_OUT_F32 0
 #define ODC_OUT_BF16 1

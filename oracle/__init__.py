@@ -354,3 +354,50 @@ def retrieve_batched(acc_arenas, out_arenas, numel, shard_off, scale: float = 1.
                                              float(np.float32(scale)), 1 if to_bf16 else 0)
     if rc != 0:
         raise MemoryError("oracle scratch allocation failed")
+
+
+class Staging:
+    """Server-side staging of Appendix B, as plain bookkeeping around `accumulate`.
+
+    Every owner has one receive slot per client.  push(g, w): for every owner whose slot for
+    client w is empty, keep slice r of g there and mark it full; an owner whose slot is still
+    full refuses (counted) -- a client has one buffer per owner, and its requests are
+    serialised.  drain(acc): every owner adds its full slots to its accumulator in ascending
+    client order, one contribution after the other, and empties them.
+    """
+
+    def __init__(self, numel, R: int, shard_off=None, full_off=None):
+        self.numel = [int(n) for n in numel]
+        self.R = R
+        self.shard_off = list(shard_off) if shard_off is not None else [0] * len(self.numel)
+        self.full_off = list(full_off) if full_off is not None else [0] * len(self.numel)
+        self.slot = {}
+        self.full = [[False] * R for _ in range(R)]
+        self.refused = 0
+
+    def push(self, g_full: np.ndarray, worker: int) -> None:
+        for r in range(self.R):
+            if self.full[r][worker]:
+                self.refused += 1
+            else:
+                self.slot[(r, worker)] = g_full.copy()
+                self.full[r][worker] = True
+
+    def drain(self, acc_arenas) -> int:
+        done = 0
+        for r in range(self.R):
+            for w in range(self.R):
+                if not self.full[r][w]:
+                    continue
+                g = self.slot.pop((r, w))
+                for t, n in enumerate(self.numel):
+                    S = shard_elems(n, self.R)
+                    lo, hi = r * S, min((r + 1) * S, n)
+                    if hi <= lo:
+                        continue
+                    views = [a[self.shard_off[t]:self.shard_off[t] + S] for a in acc_arenas]
+                    accumulate(np.ascontiguousarray(g[self.full_off[t]:self.full_off[t] + n]), views, n,
+                               ranges=[(lo, hi)])
+                self.full[r][w] = False
+                done += 1
+        return done

@@ -32,7 +32,9 @@ EXPORTS = (
     "odc_init_layout", "odc_free_layout", "odc_num_ranks", "odc_num_tensors", "odc_numel",
     "odc_shard_elems", "odc_valid_elems", "odc_rank_arena_elems", "odc_full_elems",
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
-    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
+    "odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count", "odc_stage_init",
+    "odc_stage_push", "odc_stage_drain", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
 _i64 = ctypes.c_int64
@@ -89,6 +91,15 @@ def lib():
         L.odc_scatter_accumulate_multi.restype = _int
         L.odc_scatter_accumulate_multi.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                                                    ctypes.POINTER(_int), ctypes.POINTER(_int), _int, _vp]
+        for name in ("odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count"):
+            getattr(L, name).restype = _i64
+            getattr(L, name).argtypes = [_vp]
+        L.odc_stage_init.restype = _int
+        L.odc_stage_init.argtypes = [_vp, _vp, _vp]
+        L.odc_stage_push.restype = _int
+        L.odc_stage_push.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _vp, _int, _vp]
+        L.odc_stage_drain.restype = _int
+        L.odc_stage_drain.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, ctypes.POINTER(_vp), _vp]
         L.odc_retrieve_grads.restype = _int
         L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
@@ -235,6 +246,30 @@ class Layout:
         if rc != ODC_OK:
             raise OdcError(rc, "odc_scatter_accumulate_multi")
 
+    def stage_slot_elems(self) -> int:
+        return lib().odc_stage_slot_elems(self._h)
+
+    def stage_flag_count(self) -> int:
+        return lib().odc_stage_flag_count(self._h)
+
+    def stage_snapshot_count(self) -> int:
+        return lib().odc_stage_snapshot_count(self._h)
+
+    def stage_init(self, flags, stream=None) -> None:
+        rc = lib().odc_stage_init(self._h, _ptr(flags), _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_stage_init")
+
+    def stage_push(self, grad_full, staging_shards, flags, worker: int, stream=None) -> None:
+        rc = stage_push_rc(self, grad_full, staging_shards, flags, worker, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_stage_push")
+
+    def stage_drain(self, staging_shards, flags, snapshot, accum_shards, stream=None) -> None:
+        rc = stage_drain_rc(self, staging_shards, flags, snapshot, accum_shards, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_stage_drain")
+
     def retrieve_grads(self, accum_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
                        stream=None) -> None:
         rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
@@ -268,6 +303,16 @@ def scatter_accumulate_multi_rc(layout: Layout, grads, accum_shards, workers, mi
     marr = (_int * max(k, 1))(*[int(m) for m in microbatches])
     return lib().odc_scatter_accumulate_multi(layout.handle, k, garr, _ptr_array(accum_shards, layout.R), warr,
                                               marr, int(flags), _stream(stream))
+
+
+def stage_push_rc(layout: Layout, grad_full, staging_shards, flags, worker: int, stream=None) -> int:
+    return lib().odc_stage_push(layout.handle, _ptr(grad_full), _ptr_array(staging_shards, layout.R), _ptr(flags),
+                                int(worker), _stream(stream))
+
+
+def stage_drain_rc(layout: Layout, staging_shards, flags, snapshot, accum_shards, stream=None) -> int:
+    return lib().odc_stage_drain(layout.handle, _ptr_array(staging_shards, layout.R), _ptr(flags), _ptr(snapshot),
+                                 _ptr_array(accum_shards, layout.R), _stream(stream))
 
 
 def retrieve_grads_rc(layout: Layout, accum_shards, out_shards, scale: float = 1.0,

@@ -297,6 +297,88 @@ int odc_scatter_accumulate_multi(const odc_layout_t *L, int count, const void *c
     return rc;
 }
 
+static int64_t stage_slot(const odc_layout_t *L)
+{
+    return (L->host.arena_elems + odc::kAlignElems - 1) / odc::kAlignElems * odc::kAlignElems;
+}
+
+int64_t odc_stage_slot_elems(const odc_layout_t *L) { return L ? stage_slot(L) : -1; }
+
+int64_t odc_stage_flag_count(const odc_layout_t *L)
+{
+    return L ? static_cast<int64_t>(L->host.R) * L->host.R + 1 : -1;
+}
+
+int64_t odc_stage_snapshot_count(const odc_layout_t *L)
+{
+    return L ? static_cast<int64_t>(L->host.R) * (L->host.R + 1) : -1;
+}
+
+int odc_stage_init(const odc_layout_t *L, void *flags, void *stream)
+{
+    if (!L || !flags) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(flags)) return ODC_ERR_ALIGNMENT;
+    const int rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const int e = odc::launch_stage_zero(flags, odc_stage_flag_count(L), stream);
+    return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
+}
+
+int odc_stage_push(const odc_layout_t *L, const void *grad_full, void *const *staging_shards, void *flags,
+                   int worker, void *stream)
+{
+    int rc = check_launchable(L, staging_shards);
+    if (rc != ODC_OK) return rc;
+    if (!grad_full || !flags || worker < 0 || worker >= L->host.R) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(grad_full) || !aligned16(flags)) return ODC_ERR_ALIGNMENT;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    const int64_t slot = stage_slot(L);
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        int e;
+        if (H.T == 1)
+            e = odc::launch_stage_push_flat(staging_shards + r0, r0, nr, grad_full, flags, H.desc[0].S,
+                                            H.desc[0].numel, slot, H.R, worker, stream);
+        else
+            e = odc::launch_stage_push_batched(L->table, staging_shards + r0, r0, nr, grad_full, flags, slot, H.R,
+                                               worker, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    const int e = odc::launch_stage_raise(flags, H.R, worker, stream);
+    return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
+}
+
+int odc_stage_drain(const odc_layout_t *L, const void *const *staging_shards, void *flags, void *snapshot,
+                    void *const *accum_shards, void *stream)
+{
+    int rc = check_launchable(L, staging_shards);
+    if (rc != ODC_OK) return rc;
+    rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (!flags || !snapshot) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(flags) || !aligned16(snapshot)) return ODC_ERR_ALIGNMENT;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    const int64_t slot = stage_slot(L);
+    int e = odc::launch_stage_snapshot(flags, snapshot, H.R, stream);
+    if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        if (H.T == 1)
+            e = odc::launch_stage_drain_flat(accum_shards + r0, staging_shards + r0, r0, nr, snapshot, H.desc[0].S,
+                                             H.desc[0].numel, slot, H.R, stream);
+        else
+            e = odc::launch_stage_drain_batched(L->table, accum_shards + r0, staging_shards + r0, r0, nr, snapshot,
+                                                slot, H.R, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    e = odc::launch_stage_clear(flags, snapshot, H.R, stream);
+    return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
+}
+
 int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, void *const *out_shards,
                        float scale, int out_dtype, void *stream)
 {

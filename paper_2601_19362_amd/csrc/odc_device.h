@@ -899,6 +899,223 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
     }
 }
 
+// --------------------------------------------------------------------------------- staging
+// Server-side staging (paper Appendix B): every owner keeps one receive buffer per client
+// (M/N elements each, M per owner in total).  A worker's push copies slice r of its gradient
+// into its own slot of owner r's staging buffer and then raises flag (r, w); the owner's
+// drain takes a snapshot of its flags and, in one pass over its accumulator, adds every
+// staged slice in ascending client order -- the same left-to-right binary32 sequence as
+// single contributions in that order -- then lowers the flags it consumed.  The polling
+// daemon of the paper becomes a drain call that handles whatever has arrived and returns;
+// no kernel ever waits.
+//
+// Layout: owner r's staging buffer holds R slots of `slot` elements (the rank arena length
+// rounded up to 8, so every slot starts 16-byte aligned); client w's slot starts at w * slot
+// and mirrors the rank arena element for element.  flags[r * R + w] is 0 (empty) or 1 (full);
+// flags[R * R] counts refused pushes (a slot that is still full is never overwritten).
+
+// Copy `valid` bf16 elements from an unaligned source to a 16-byte-aligned destination.
+template <int TPB, bool NT>
+__device__ __forceinline__ void copy_to_aligned(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                int64_t valid)
+{
+    const int64_t nvec = valid >> 3;
+    const int tail = static_cast<int>(valid & 7);
+    const int64_t ntiles = (nvec + TPB - 1) / TPB;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t v = tile * TPB + threadIdx.x;
+        if (v < nvec) st<NT>(reinterpret_cast<u32x4 *>(dst) + v, ld_u128_unaligned<NT>(src + 8 * v));
+    }
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
+        const int64_t k = 8 * nvec + threadIdx.x;
+        st_u16(dst + k, ld_u16(src + k));
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(64) void k_stage_push_flat(RankPtrs staging, const uint16_t *__restrict__ grad,
+                                                        const int32_t *__restrict__ flags, int64_t S, int64_t N,
+                                                        int64_t slot, int R, int r0, int worker)
+{
+    const int r = r0 + static_cast<int>(blockIdx.y);
+    const int64_t base = static_cast<int64_t>(r) * S;
+    int64_t valid = N - base;
+    if (valid > S) valid = S;
+    if (valid <= 0) return;
+    if (flags[static_cast<int64_t>(r) * R + worker] != 0) return;  // slot still full: refuse
+    uint16_t *dst = static_cast<uint16_t *>(staging.p[blockIdx.y]) + static_cast<int64_t>(worker) * slot;
+    copy_to_aligned<64, NT>(grad + base, dst, valid);
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable tb, RankPtrs staging,
+                                                                      const uint16_t *__restrict__ grad,
+                                                                      const int32_t *__restrict__ flags,
+                                                                      int64_t slot, int R, int r0, int nr, int worker)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t nwork = ntiles * nr;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / nr;
+        const int rl = static_cast<int>(work - tile * nr);
+        const int r = r0 + rl;
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        if (flags[static_cast<int64_t>(r) * R + worker] != 0) continue;  // uniform per workgroup
+        uint16_t *dst = static_cast<uint16_t *>(staging.p[rl]) + static_cast<int64_t>(worker) * slot;
+        const int a_rel = 8 * static_cast<int>(threadIdx.x);
+        const int64_t a = (tile << kChunkShift) + a_rel;
+        if (a >= tb.arena_elems) continue;
+        const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+        const int64_t slot_in = a - d.shard_off;
+        const int cnt = valid_from(d, r, slot_in, 8);
+        const uint16_t *src = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot_in;
+        if (cnt == 8) st<NT>(reinterpret_cast<u32x4 *>(dst + a), ld_u128_unaligned<NT>(src));
+        else
+            for (int e = 0; e < cnt; ++e) st_u16(dst + a + e, ld_u16(src + e));
+    }
+}
+
+// flags[r * R + worker] = 1 for the owners whose slot was empty; a refused push is counted.
+__global__ __launch_bounds__(64) void k_stage_raise(int32_t *flags, int R, int worker)
+{
+    for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
+        ODC_GLOBAL int32_t *f = (ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R + worker);
+        if (*f == 0) *f = 1;
+        else atomicAdd(flags + static_cast<int64_t>(R) * R, 1);
+    }
+}
+
+// One thread per owner.  Snapshot: the owner's full slots, ascending, are written as a list
+// snapshot[r * (R + 1)] = count, then the client indices.  Clear: every listed flag is lowered.
+// Taking the list once per drain keeps all workgroups of the accumulate kernel on the same set
+// of contributions even if pushes from other streams raise more flags meanwhile.
+__global__ __launch_bounds__(64) void k_stage_snapshot(const int32_t *flags, int32_t *snapshot, int R)
+{
+    for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
+        ODC_GLOBAL int32_t *list = (ODC_GLOBAL int32_t *)(snapshot + static_cast<int64_t>(r) * (R + 1));
+        const ODC_GLOBAL int32_t *row = (const ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R);
+        int n = 0;
+        for (int w = 0; w < R; ++w)
+            if (row[w] != 0) list[1 + n++] = w;
+        list[0] = n;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_stage_clear(int32_t *flags, const int32_t *snapshot, int R)
+{
+    for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
+        const ODC_GLOBAL int32_t *list = (const ODC_GLOBAL int32_t *)(snapshot + static_cast<int64_t>(r) * (R + 1));
+        ODC_GLOBAL int32_t *row = (ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R);
+        const int n = list[0];
+        for (int k = 0; k < n; ++k) row[list[1 + k]] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_stage_zero(int32_t *flags, int64_t count)
+{
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < count; i += static_cast<int64_t>(gridDim.x) * 256)
+        *(ODC_GLOBAL int32_t *)(flags + i) = 0;
+}
+
+// Add the staged vectors of the listed clients, in list order, to one accumulator vector;
+// up to four staged vectors are fetched before they are added.  `list` is the owner's
+// snapshot (count, then client indices): the same for every lane, so its reads are scalar.
+template <bool NT>
+__device__ __forceinline__ f32x4 drain_vec(f32x4 acc, const uint16_t *__restrict__ stage, int64_t slot, int64_t a,
+                                           const int32_t *__restrict__ list)
+{
+    constexpr int B = 4;
+    const int n = list[0];
+    for (int c = 0; c < n; c += B) {
+        u32x2 gv[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (c + j < n)
+                gv[j] = ld<NT>(reinterpret_cast<const u32x2 *>(stage + static_cast<int64_t>(list[1 + c + j]) * slot + a));
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (c + j < n) acc = add4<false>(acc, gv[j], 1.0f);
+    }
+    return acc;
+}
+
+__device__ __forceinline__ float drain_one(float v, const uint16_t *__restrict__ stage, int64_t slot, int64_t k,
+                                           const int32_t *__restrict__ list)
+{
+    const int n = list[0];
+    for (int c = 0; c < n; ++c) v = v + widen_one(ld_u16(stage + static_cast<int64_t>(list[1 + c]) * slot + k));
+    return v;
+}
+
+template <bool NT>
+__global__ __launch_bounds__(64) void k_stage_drain_flat(RankPtrs accs, RankPtrs staging,
+                                                         const int32_t *__restrict__ snapshot, int64_t S, int64_t N,
+                                                         int64_t slot, int R, int r0)
+{
+    const int r = r0 + static_cast<int>(blockIdx.y);
+    const int64_t base = static_cast<int64_t>(r) * S;
+    int64_t valid = N - base;
+    if (valid > S) valid = S;
+    if (valid <= 0) return;
+    const int32_t *list = snapshot + static_cast<int64_t>(r) * (R + 1);
+    if (list[0] == 0) return;  // nothing staged for this owner: its accumulator is not touched
+    float *__restrict__ acc = static_cast<float *>(accs.p[blockIdx.y]);
+    const uint16_t *__restrict__ stage = static_cast<const uint16_t *>(staging.p[blockIdx.y]);
+    const int64_t nitem = valid >> 2;
+    const int tail = static_cast<int>(valid & 3);
+    const int64_t ntiles = (nitem + 63) >> 6;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t q = (tile << 6) + threadIdx.x;
+        if (q < nitem) {
+            f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
+            st<NT>(av, drain_vec<NT>(ld<NT>(av), stage, slot, 4 * q, list));
+        }
+    }
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
+        const int64_t k = 4 * nitem + threadIdx.x;
+        st_f32(acc + k, drain_one(ld_f32(acc + k), stage, slot, k, list));
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTable tb, RankPtrs accs, RankPtrs staging,
+                                                                       const int32_t *__restrict__ snapshot,
+                                                                       int64_t slot, int R, int r0, int nr)
+{
+    __shared__ TileIndex<1> lds;
+    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t nwork = ntiles * nr;
+    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
+        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
+        const int64_t tile = work / nr;
+        const int rl = static_cast<int>(work - tile * nr);
+        const int r = r0 + rl;
+        int t_lo, n;
+        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        const int32_t *list = snapshot + static_cast<int64_t>(r) * (R + 1);
+        if (list[0] == 0) continue;
+        float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
+        const uint16_t *__restrict__ stage = static_cast<const uint16_t *>(staging.p[rl]);
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = (tile << kChunkShift) + a_rel;
+            if (a >= tb.arena_elems) continue;
+            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const int cnt = valid_from(d, r, a - d.shard_off, 4);
+            if (cnt == 4) {
+                f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);
+                st<NT>(av, drain_vec<NT>(ld<NT>(av), stage, slot, a, list));
+            } else {
+                for (int e = 0; e < cnt; ++e) st_f32(arena + a + e, drain_one(ld_f32(arena + a + e), stage, slot, a + e, list));
+            }
+        }
+    }
+}
+
 // -------------------------------------------------------------------------------- retrieve
 // Minibatch-end retrieval (paper Section 3.2): each owner's accumulated gradient shard is
 // read, multiplied by `scale` (one binary32 multiply) and written to the owner's output shard

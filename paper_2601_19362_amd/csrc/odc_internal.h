@@ -112,6 +112,19 @@ int launch_accum_multi_flat(void *const *ptrs, int r0, int nr, const void *const
                             int64_t N, bool atomic, void *stream);
 int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *const *grads,
                                int count, bool atomic, void *stream);
+// Staging (per-client receive buffers + flags); see odc_stage_* in odc.h.
+int launch_stage_zero(void *flags, int64_t count, void *stream);
+int launch_stage_push_flat(void *const *staging, int r0, int nr, const void *grad, const void *flags, int64_t S,
+                           int64_t N, int64_t slot, int R, int worker, void *stream);
+int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0, int nr, const void *grad,
+                              const void *flags, int64_t slot, int R, int worker, void *stream);
+int launch_stage_raise(void *flags, int R, int worker, void *stream);
+int launch_stage_snapshot(const void *flags, void *snapshot, int R, void *stream);
+int launch_stage_clear(void *flags, const void *snapshot, int R, void *stream);
+int launch_stage_drain_flat(void *const *accs, const void *const *staging, int r0, int nr, const void *snapshot,
+                            int64_t S, int64_t N, int64_t slot, int R, void *stream);
+int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const void *const *staging, int r0, int nr,
+                               const void *snapshot, int64_t slot, int R, void *stream);
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream);
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,

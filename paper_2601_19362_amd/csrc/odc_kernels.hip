@@ -225,6 +225,84 @@ int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, 
     return finish();
 }
 
+int launch_stage_zero(void *flags, int64_t count, void *stream)
+{
+    const unsigned blocks = grid_x_for(count, 256, 1024);
+    k_stage_zero<<<dim3(blocks), 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t *>(flags), count);
+    return finish();
+}
+
+int launch_stage_push_flat(void *const *staging, int r0, int nr, const void *grad, const void *flags, int64_t S,
+                           int64_t N, int64_t slot, int R, int worker, void *stream)
+{
+    const RankPtrs rp = pack(staging, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                    (k_stage_push_flat<NT_><<<plain_grid((S >> 3) + 1, 64, nr), 64, 0, s>>>(
+                        rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), S, N, slot, R,
+                        r0, worker)));
+    return finish();
+}
+
+int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0, int nr, const void *grad,
+                              const void *flags, int64_t slot, int R, int worker, void *stream)
+{
+    const RankPtrs rp = pack(staging, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                    (k_stage_push_batched<NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                        tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,
+                        nr, worker)));
+    return finish();
+}
+
+int launch_stage_raise(void *flags, int R, int worker, void *stream)
+{
+    k_stage_raise<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t *>(flags), R,
+                                                                                   worker);
+    return finish();
+}
+
+int launch_stage_snapshot(const void *flags, void *snapshot, int R, void *stream)
+{
+    k_stage_snapshot<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const int32_t *>(flags), static_cast<int32_t *>(snapshot), R);
+    return finish();
+}
+
+int launch_stage_clear(void *flags, const void *snapshot, int R, void *stream)
+{
+    k_stage_clear<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<int32_t *>(flags), static_cast<const int32_t *>(snapshot), R);
+    return finish();
+}
+
+int launch_stage_drain_flat(void *const *accs, const void *const *staging, int r0, int nr, const void *snapshot,
+                            int64_t S, int64_t N, int64_t slot, int R, void *stream)
+{
+    const RankPtrs ra = pack(accs, nr);
+    const RankPtrs rs = pack(staging, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                    (k_stage_drain_flat<NT_><<<plain_grid((S >> 2) + 1, 64, nr), 64, 0, s>>>(
+                        ra, rs, static_cast<const int32_t *>(snapshot), S, N, slot, R, r0)));
+    return finish();
+}
+
+int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const void *const *staging, int r0, int nr,
+                               const void *snapshot, int64_t slot, int R, void *stream)
+{
+    const RankPtrs ra = pack(accs, nr);
+    const RankPtrs rs = pack(staging, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                    (k_stage_drain_batched<NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                        tb, ra, rs, static_cast<const int32_t *>(snapshot), slot, R, r0, nr)));
+    return finish();
+}
+
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream)
 {

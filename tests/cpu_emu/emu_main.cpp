@@ -143,6 +143,7 @@ int main(int argc, char **argv)
     const int R = std::atoi(argv[3]);
     int threads = 256, unroll = 4, nt = 1, remap = 0, atomic = 0, cap = 0, rg = 1, weighted = 0, bf16 = 0, count = 2;
     float weight = 1.0f, scale = 1.0f;
+    std::string script;
     for (int k = 4; k < argc; ++k) {
         const std::string kv = argv[k];
         const size_t eq = kv.find('=');
@@ -158,6 +159,7 @@ int main(int argc, char **argv)
         else if (key == "weighted") weighted = std::atoi(val.c_str());
         else if (key == "bf16") bf16 = std::atoi(val.c_str());
         else if (key == "count") count = std::atoi(val.c_str());
+        else if (key == "script") script = val;
         else if (key == "weight") weight = std::strtof(val.c_str(), nullptr);
         else if (key == "scale") scale = std::strtof(val.c_str(), nullptr);
         else {
@@ -327,6 +329,88 @@ int main(int argc, char **argv)
         write_file(dir + "/acc.out", out.data(), out.size());
         for (auto *b : bufs) std::free(b);
         for (auto *g : gbufs) std::free(g);
+        return 0;
+    }
+
+    if (op == "stage") {
+        // script: comma-separated steps; "pW" = push by worker W (k-th push reads grad<k>.u16), "d" = drain
+        std::vector<float> all = read_file<float>(dir + "/acc.f32");
+        if (all.size() != arena * static_cast<size_t>(R)) return 4;
+        const int64_t slot = (H.arena_elems + kAlignElems - 1) / kAlignElems * kAlignElems;
+        std::vector<float *> accs(static_cast<size_t>(R));
+        std::vector<uint16_t *> stages(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            accs[r] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(accs[r], all.data() + arena * r, arena * 4);
+            stages[r] = static_cast<uint16_t *>(std::malloc(static_cast<size_t>(slot) * R * 2));
+            std::memset(stages[r], 0xEE, static_cast<size_t>(slot) * R * 2);
+        }
+        const size_t nflags = static_cast<size_t>(R) * R + 1, nsnap = static_cast<size_t>(R) * (R + 1);
+        int32_t *flags = static_cast<int32_t *>(std::malloc(nflags * 4));
+        int32_t *snap = static_cast<int32_t *>(std::malloc(nsnap * 4));
+        std::memset(flags, 0x55, nflags * 4);
+        run_grid(256, grid_x_for(static_cast<int64_t>(nflags), 256, 1024), 1, [&] { k_stage_zero(flags, static_cast<int64_t>(nflags)); });
+        int pushes = 0;
+        size_t pos = 0;
+        while (pos < script.size()) {
+            size_t comma = script.find(',', pos);
+            if (comma == std::string::npos) comma = script.size();
+            const std::string step = script.substr(pos, comma - pos);
+            pos = comma + 1;
+            if (step[0] == 'p') {
+                const int worker = std::atoi(step.c_str() + 1);
+                std::vector<uint16_t> gi = read_file<uint16_t>(dir + "/grad" + std::to_string(pushes++) + ".u16");
+                if (gi.size() != full_n) return 4;
+                uint16_t *g = static_cast<uint16_t *>(std::malloc(full_n * 2));
+                std::memcpy(g, gi.data(), full_n * 2);
+                for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+                    const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+                    RankPtrs rs{};
+                    for (int k = 0; k < nr; ++k) rs.p[k] = stages[r0 + k];
+                    if (flat) {
+                        EMU_NT(nt, run_grid(64, grid_x_for((S >> 3) + 1, 64, cap), nr, [&] {
+                                   k_stage_push_flat<NT_>(rs, g, flags, S, N, slot, R, r0, worker);
+                               }));
+                    } else {
+                        const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                                   k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, nr, worker);
+                               }));
+                    }
+                }
+                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_raise(flags, R, worker); });
+                std::free(g);
+            } else {
+                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_snapshot(flags, snap, R); });
+                for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+                    const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+                    RankPtrs ra{}, rs{};
+                    for (int k = 0; k < nr; ++k) {
+                        ra.p[k] = accs[r0 + k];
+                        rs.p[k] = stages[r0 + k];
+                    }
+                    if (flat) {
+                        EMU_NT(nt, run_grid(64, grid_x_for((S >> 2) + 1, 64, cap), nr, [&] {
+                                   k_stage_drain_flat<NT_>(ra, rs, snap, S, N, slot, R, r0);
+                               }));
+                    } else {
+                        const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                                   k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0, nr);
+                               }));
+                    }
+                }
+                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_clear(flags, snap, R); });
+            }
+        }
+        std::vector<float> out(arena * static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) std::memcpy(out.data() + arena * r, accs[r], arena * 4);
+        write_file(dir + "/acc.out", out.data(), out.size());
+        write_file(dir + "/flags.out", flags, nflags);
+        for (auto *b : accs) std::free(b);
+        for (auto *b : stages) std::free(b);
+        std::free(flags);
+        std::free(snap);
         return 0;
     }
 

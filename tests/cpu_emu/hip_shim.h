@@ -39,3 +39,10 @@ static inline float __uint_as_float(uint32_t u)
 }
 
 static inline void unsafeAtomicAdd(float *a, float v) { *a = *a + v; }
+
+static inline int atomicAdd(int32_t *p, int v)
+{
+    const int old = *p;
+    *p = old + v;
+    return old;
+}

@@ -376,3 +376,91 @@ def test_fused_unordered_within_tolerance(oracle):
     got = np.concatenate([a[:S] for a in case.acc_host()])[:N].astype(np.float64)
     assert (np.abs(got - ref) <= 1e-6 * mag).all()
     case.close()
+
+
+# ----------------------------------------------------------------------------- staging
+class DeviceStaging:
+    def __init__(self, case):
+        L = case.layout
+        self.slot = L.stage_slot_elems()
+        self.bufs = [torch.full((case.R * self.slot,), -3.0, dtype=torch.bfloat16, device="cuda") for _ in range(case.R)]
+        self.flags = torch.full((L.stage_flag_count(),), 77, dtype=torch.int32, device="cuda")
+        self.snap = torch.zeros(L.stage_snapshot_count(), dtype=torch.int32, device="cuda")
+        L.stage_init(self.flags)
+
+
+@pytest.mark.parametrize("numel,R", [([1_048_589], 4), ([1], 64), ([4099], 8), ([3_000_001], 16), ([350], 70),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+                                     ([30000, 17, 2048, 2049, 1_000_001], 5), ([5] * 70 + [100_000], 70)])
+def test_staging_push_and_drain(oracle, numel, R):
+    case = DeviceCase(R, numel, with_params=False)
+    st = DeviceStaging(case)
+    model = oracle.Staging(numel, R, case.shard_off, case.full_off)
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    case.layout.reset_accum(case.acc_ptrs)
+    oracle.reset_batched(acc_host, numel, case.shard_off)
+    hi = R - 1
+    steps = [("p", hi), ("p", 0), ("d", None), ("p", 0), ("p", 0), ("p", min(1, hi)), ("p", min(2, hi)), ("d", None),
+             ("d", None), ("p", hi)]
+    for k, (kind, w) in enumerate(steps):
+        if kind == "p":
+            g = inputs.normal_bf16(case.full_n, 1e-2, seed=(90, k))
+            case.grad.t.copy_(to_dev_u16(g))
+            case.layout.stage_push(case.grad.t, st.bufs, st.flags, w)
+            model.push(g, w)
+        else:
+            case.layout.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs)
+            model.drain(acc_host)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"staged accumulate rank {r}")
+    flags = st.flags.cpu().numpy()
+    assert flags[:R * R].reshape(R, R).astype(bool).tolist() == model.full
+    assert flags[R * R] == model.refused
+    case.check_guards()
+    case.close()
+
+
+def test_staging_concurrent_push_and_drain_loses_nothing():
+    """Pushes on one stream, drains on another, no ordering between them: whichever drain
+    picks a contribution up, each is added exactly once.  Integer-valued gradients make every
+    sum exact, so the final result does not depend on the grouping."""
+    N, R = 3_000_001, 8
+    case = DeviceCase(R, [N], with_params=False)
+    st = DeviceStaging(case)
+    other_snap = torch.zeros_like(st.snap)
+    case.layout.reset_accum(case.acc_ptrs)
+    rng = np.random.default_rng(5)
+    ints = [rng.integers(-100, 101, size=N) for _ in range(R)]
+    grads = [to_dev_u16(inputs.f32_to_bf16_bits(v.astype(np.float32))) for v in ints]
+    torch.cuda.synchronize()
+    s_push, s_drain = torch.cuda.Stream(), torch.cuda.Stream()
+    for w in range(R):
+        case.layout.stage_push(grads[w], st.bufs, st.flags, w, stream=s_push)
+        if w % 2 == 1:
+            case.layout.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs, stream=s_drain)
+    torch.cuda.synchronize()
+    case.layout.stage_drain(st.bufs, st.flags, other_snap, case.acc_ptrs)      # whatever is left
+    torch.cuda.synchronize()
+    total = sum(ints).astype(np.float32)
+    S = case.S[0]
+    got = np.concatenate([a[:S] for a in case.acc_host()])[:N]
+    assert np.array_equal(got, total)
+    flags = st.flags.cpu().numpy()
+    assert not flags.any()
+    case.close()
+
+
+def test_staging_argument_errors():
+    case = DeviceCase(4, [1000], with_params=False)
+    st = DeviceStaging(case)
+    L = case.layout
+    assert odc.stage_push_rc(L, case.grad.t, st.bufs, st.flags, 4) == odc.ODC_ERR_INVALID_ARG
+    assert odc.stage_push_rc(L, case.grad.t, st.bufs, None, 0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.stage_push_rc(L, case.grad.t, st.bufs, st.flags[1:], 0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.stage_drain_rc(L, st.bufs, st.flags, None, case.acc_ptrs) == odc.ODC_ERR_INVALID_ARG
+    assert odc.stage_drain_rc(L, st.bufs, st.flags, st.snap, None) == odc.ODC_ERR_INVALID_ARG
+    assert L.stage_slot_elems() == 256 and L.stage_flag_count() == 17 and L.stage_snapshot_count() == 20
+    assert odc.stage_push_rc(L, case.grad.t, st.bufs, st.flags, 0) == 0
+    assert odc.stage_drain_rc(L, st.bufs, st.flags, st.snap, case.acc_ptrs) == 0
+    torch.cuda.synchronize()
+    case.close()

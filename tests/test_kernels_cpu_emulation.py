@@ -183,3 +183,37 @@ def test_emulated_fused_accumulate(oracle, emu, tmp_path, numel, R, count, cap):
     run(emu, tmp_path, "accum_multi", R, count=count, cap=cap)
     got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+
+
+@pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([4099], 8), ([1], 64),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5),
+                                     ([5] * 66, 66)])
+@pytest.mark.parametrize("nt,cap", [(1, 0), (0, 2)])
+def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
+    """Pushes into per-client slots, drains in ascending client order, refusal of a push into
+    a slot that is still full; compared with the oracle's bookkeeping model."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc, numel, so)
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    w_hi = R - 1
+    steps = [("p", w_hi), ("p", 0), ("d", None), ("p", 0), ("p", 0), ("p", min(1, w_hi)), ("d", None), ("d", None),
+             ("p", w_hi)]
+    model = oracle.Staging(numel, R, so, fo)
+    k = 0
+    for kind, w in steps:
+        if kind == "p":
+            g = inputs.normal_bf16(full_n, 1e-2, seed=(9, k))
+            g.tofile(tmp_path / f"grad{k}.u16")
+            k += 1
+            model.push(g, w)
+        else:
+            model.drain(acc)
+    script = ",".join(f"p{w}" if kind == "p" else "d" for kind, w in steps)
+    run(emu, tmp_path, "stage", R, nt=nt, cap=cap, script=script)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+    flags = np.fromfile(tmp_path / "flags.out", dtype=np.int32)
+    assert flags[:R * R].reshape(R, R).astype(bool).tolist() == model.full
+    assert flags[R * R] == model.refused and model.refused >= R     # at least the second push of worker 0

@@ -430,3 +430,35 @@ def test_planted_mistakes_are_caught():
         for w in range(2):
             mw = np.float32(mw + np.float32(vals.get((w, m), 0.0)))
     assert wm != mw
+
+
+def test_staging_model_is_ordered_accumulation_by_client(oracle):
+    """The staging bookkeeping (Appendix B: one receive slot per client and owner) against
+    plain ordered accumulation written out here: a drain adds the staged gradients in
+    ascending client order; a push into a slot that is still full is refused."""
+    N, R = 1001, 4
+    S = -(-N // R)
+    gs = {k: inputs.normal_bf16(N, 1e-3, seed=(70, k)) for k in range(5)}
+    st = oracle.Staging([N], R)
+    acc = new_acc(S, R)
+    ref = new_acc(S, R)
+    oracle.reset(acc, N)
+    oracle.reset(ref, N)
+    st.push(gs[0], 3)
+    st.push(gs[1], 1)
+    st.push(gs[2], 3)            # refused by every owner: slot (r, 3) is still full
+    assert st.refused == R
+    assert st.drain(acc) == 2 * R
+    oracle.accumulate(gs[1], ref, N)   # client 1 before client 3
+    oracle.accumulate(gs[0], ref, N)
+    for a, b in zip(acc, ref):
+        assert np.array_equal(bits32(a), bits32(b))
+    assert st.drain(acc) == 0          # nothing staged: nothing changes
+    st.push(gs[3], 3)
+    st.push(gs[4], 0)
+    st.drain(acc)
+    oracle.accumulate(gs[4], ref, N)
+    oracle.accumulate(gs[3], ref, N)
+    for a, b in zip(acc, ref):
+        assert np.array_equal(bits32(a), bits32(b))
+    assert not any(any(row) for row in st.full)
