@@ -248,6 +248,7 @@ int odc_last_hip_error(void);
  *   "gather_unroll" / "accum_unroll" / "reset_unroll"     16-byte work items per thread: 1, 2, 4
  *   "nontemporal"   0 or 1: streaming accesses carry the non-temporal hint
  *   "tile_remap"    0 or 1: each XCD sweeps its own contiguous eighth of the tiles
+ *   "gather_store_sc1"  0 or 1: single-tensor gather stores carry sc1 + nt instead of nt
  *   "max_grid_x"    0 = one workgroup per tile; > 0 caps the grid, workgroups then loop
  *   "batch_rank_group"  owners handled by one workgroup of the multi-tensor accumulate and
  *                   reset kernels: 0 = chosen from the launch size, or 1, 2, 4, 8

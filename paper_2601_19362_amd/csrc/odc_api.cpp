@@ -468,6 +468,7 @@ int odc_tune(const char *knob, int value)
     else if (!std::strcmp(knob, "reset_threads") && threads_ok) t.reset_threads = value;
     else if (!std::strcmp(knob, "nontemporal") && flag_ok) t.nontemporal = value;
     else if (!std::strcmp(knob, "tile_remap") && flag_ok) t.tile_remap = value;
+    else if (!std::strcmp(knob, "gather_store_sc1") && flag_ok) t.gather_store_sc1 = value;
     else if (!std::strcmp(knob, "max_grid_x") && value >= 0) t.max_grid_x = value;
     else if (!std::strcmp(knob, "batch_rank_group") &&
              (value == 0 || value == 1 || value == 2 || value == 4 || value == 8))

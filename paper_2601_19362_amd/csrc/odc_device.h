@@ -65,6 +65,47 @@ __device__ __forceinline__ void st(V *p, V v)
     else *q = v;
 }
 
+// Stores with the non-temporal hint and system-scope write-through (sc1 nt).  For streams
+// that are only written (gather output, reset, retrieval, staging) this measured about 3 %
+// faster than the plain non-temporal store; the compiler has no builtin for the combination,
+// so the store is written as one instruction.  It is an ordinary vector store: the only
+// thing the compiler does not know is that it bumps the memory-operation counter, which can
+// only make a later wait longer, never too short.
+__device__ __forceinline__ void st_sc1_nt(u32x4 *p, u32x4 v)
+{
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+#else
+    *p = v;
+#endif
+}
+
+__device__ __forceinline__ void st_sc1_nt(f32x4 *p, f32x4 v)
+{
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+#else
+    *p = v;
+#endif
+}
+
+__device__ __forceinline__ void st_sc1_nt(u32x2 *p, u32x2 v)
+{
+#ifdef __HIP_DEVICE_COMPILE__
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+#else
+    *p = v;
+#endif
+}
+
+// Store of a write-only stream: WT = 2 sc1 + nt, 1 nt, 0 plain.
+template <int WT, typename V>
+__device__ __forceinline__ void st_stream(V *p, V v)
+{
+    if constexpr (WT == 2) st_sc1_nt(p, v);
+    else st<WT == 1>(p, v);
+}
+
 template <bool NT>
 __device__ __forceinline__ u32x4 ld_u128_unaligned(const uint16_t *p)
 {
@@ -123,7 +164,7 @@ __device__ __forceinline__ int64_t slots_of(int64_t ntiles, int remap)
     return remap ? ((ntiles + 7) >> 3) << 3 : ntiles;
 }
 
-template <int TPB, int U, bool NT, bool GUARD>
+template <int TPB, int U, bool NT, bool GUARD, bool SC1>
 __device__ __forceinline__ void gather_tile(const uint16_t *__restrict__ bsrc, u32x4 *__restrict__ bdst,
                                             int64_t v0, int64_t nvec)
 {
@@ -136,11 +177,14 @@ __device__ __forceinline__ void gather_tile(const uint16_t *__restrict__ bsrc, u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int64_t v = v0 + u * TPB;
-        if (!GUARD || v < nvec) st<NT>(bdst + v, reg[u]);
+        if (!GUARD || v < nvec) {
+            if constexpr (SC1) st_sc1_nt(bdst + v, reg[u]);
+            else st<NT>(bdst + v, reg[u]);
+        }
     }
 }
 
-template <int TPB, int U, bool NT>
+template <int TPB, int U, bool NT, bool SC1>
 __global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *__restrict__ full,
                                                      int64_t S, int64_t N, int r0, int remap)
 {
@@ -162,8 +206,8 @@ __global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *
     const int64_t nslots = slots_of(ntiles, remap);
     for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
         const int64_t t0 = tile_of(slot, ntiles, remap) * (TPB * U);
-        if (t0 + TPB * U <= nvec) gather_tile<TPB, U, NT, false>(bsrc, bdst, t0 + threadIdx.x, nvec);
-        else if (t0 < nvec) gather_tile<TPB, U, NT, true>(bsrc, bdst, t0 + threadIdx.x, nvec);
+        if (t0 + TPB * U <= nvec) gather_tile<TPB, U, NT, false, SC1>(bsrc, bdst, t0 + threadIdx.x, nvec);
+        else if (t0 < nvec) gather_tile<TPB, U, NT, true, SC1>(bsrc, bdst, t0 + threadIdx.x, nvec);
     }
     if (blockIdx.x == 0) {
         const int t = threadIdx.x;
@@ -278,7 +322,7 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t v = v0 + u * TPB;
-            if (v < nvec) st<NT>(reinterpret_cast<f32x4 *>(acc) + v, zero);
+            if (v < nvec) st_stream<NT ? 2 : 0>(reinterpret_cast<f32x4 *>(acc) + v, zero);
         }
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) st_f32(acc + 4 * nvec + threadIdx.x, 0.0f);
@@ -924,7 +968,7 @@ __device__ __forceinline__ void copy_to_aligned(const uint16_t *__restrict__ src
     const int64_t ntiles = (nvec + TPB - 1) / TPB;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t v = tile * TPB + threadIdx.x;
-        if (v < nvec) st<NT>(reinterpret_cast<u32x4 *>(dst) + v, ld_u128_unaligned<NT>(src + 8 * v));
+        if (v < nvec) st_stream<NT ? 2 : 0>(reinterpret_cast<u32x4 *>(dst) + v, ld_u128_unaligned<NT>(src + 8 * v));
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
         const int64_t k = 8 * nvec + threadIdx.x;
@@ -1130,7 +1174,7 @@ __device__ __forceinline__ uint32_t narrow_bf16(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <bool NT, bool BF16>
+template <bool NT, bool BF16, bool STREAM>
 __device__ __forceinline__ void retrieve_vec(const float *__restrict__ src, void *__restrict__ out, int64_t q, float scale)
 {
     f32x4 v = ld<NT>(reinterpret_cast<const f32x4 *>(src) + q);
@@ -1140,9 +1184,9 @@ __device__ __forceinline__ void retrieve_vec(const float *__restrict__ src, void
     v.w = scale * v.w;
     if constexpr (BF16) {
         const u32x2 p = {narrow_bf16(v.x) | (narrow_bf16(v.y) << 16), narrow_bf16(v.z) | (narrow_bf16(v.w) << 16)};
-        st<NT>(reinterpret_cast<u32x2 *>(out) + q, p);
+        st_stream<(NT ? (STREAM ? 2 : 1) : 0)>(reinterpret_cast<u32x2 *>(out) + q, p);
     } else {
-        st<NT>(reinterpret_cast<f32x4 *>(out) + q, v);
+        st_stream<(NT ? (STREAM ? 2 : 1) : 0)>(reinterpret_cast<f32x4 *>(out) + q, v);
     }
 }
 
@@ -1172,7 +1216,7 @@ __global__ __launch_bounds__(TPB) void k_retrieve_flat(RankPtrs accs, RankPtrs o
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t v = v0 + u * TPB;
-            if (v < nvec) retrieve_vec<NT, BF16>(acc, out, v, scale);
+            if (v < nvec) retrieve_vec<NT, BF16, true>(acc, out, v, scale);
         }
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) retrieve_one<BF16>(acc, out, 4 * nvec + threadIdx.x, scale);
@@ -1205,7 +1249,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
                 const float *src = static_cast<const float *>(accs.p[rl]);
                 void *out = outs.p[rl];
                 const int cnt = valid_from(d, r0 + rl, a - d.shard_off, 4);
-                if (cnt == 4) retrieve_vec<NT, BF16>(src, out, a >> 2, scale);
+                if (cnt == 4) retrieve_vec<NT, BF16, false>(src, out, a >> 2, scale);
                 else
                     for (int e = 0; e < cnt; ++e) retrieve_one<BF16>(src, out, a + e, scale);
             }

@@ -69,9 +69,15 @@ int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int6
     const Tuning &t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH(t.gather_threads, t.gather_unroll, t.nontemporal != 0,
-                 (k_gather_flat<TPB_, U_, NT_><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
-                     rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
+    if (t.gather_store_sc1 && t.nontemporal) {
+        ODC_DISPATCH(t.gather_threads, t.gather_unroll, true,
+                     (k_gather_flat<TPB_, U_, NT_, true><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
+    } else {
+        ODC_DISPATCH(t.gather_threads, t.gather_unroll, t.nontemporal != 0,
+                     (k_gather_flat<TPB_, U_, NT_, false><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                         rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
+    }
     return finish();
 }
 

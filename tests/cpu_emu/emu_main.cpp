@@ -201,7 +201,7 @@ int main(int argc, char **argv)
             if (flat) {
                 EMU_DISPATCH(threads, unroll, nt,
                              run_grid(TPB_, gx_for((S >> 3) + 1, TPB_ * U_, cap, remap), nr, [&] {
-                                 k_gather_flat<TPB_, U_, NT_>(rp, full, S, N, r0, remap);
+                                 k_gather_flat<TPB_, U_, NT_, false>(rp, full, S, N, r0, remap);
                              }));
             } else {
                 const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;

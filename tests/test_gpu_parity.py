@@ -99,16 +99,20 @@ def test_stress_config(oracle):
          tile_remap=1),
     dict(gather_threads=256, accum_threads=128, reset_threads=64, gather_unroll=2, accum_unroll=4, reset_unroll=4,
          tile_remap=1, nontemporal=0),
+    dict(gather_threads=64, gather_unroll=1, gather_store_sc1=0),
+    dict(gather_threads=128, gather_unroll=4, gather_store_sc1=1, tile_remap=1),
 ])
 def test_results_do_not_depend_on_launch_knobs(oracle, knobs):
     """Every launch configuration gives the same bits."""
-    neutral = dict(nontemporal=1, max_grid_x=0, tile_remap=0)
+    neutral = dict(nontemporal=1, max_grid_x=0, tile_remap=0, gather_store_sc1=1)
     try:
         for k, v in {**neutral, **knobs}.items():
             odc.tune(k, v)
         run_case(oracle, [2_000_003], 4, [(0, 0), (1, 0), (1, 1)], seed=77)
         run_case(oracle, [1_000_000], 8, [(0, 0)], seed=79)
         run_case(oracle, [30000, 17, 2048, 2049, 100_001], 5, [(0, 0), (4, 2)], seed=78)
+        weighted_retrieve_case(oracle, [1_500_007], 4, seed=80, weights=[0.37, None], scale=1.0 / 3.0)
+        staging_case(oracle, [1_000_003], 4)
     finally:
         odc.reset_tuning()
 
@@ -393,6 +397,10 @@ class DeviceStaging:
                                      ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
                                      ([30000, 17, 2048, 2049, 1_000_001], 5), ([5] * 70 + [100_000], 70)])
 def test_staging_push_and_drain(oracle, numel, R):
+    staging_case(oracle, numel, R)
+
+
+def staging_case(oracle, numel, R):
     case = DeviceCase(R, numel, with_params=False)
     st = DeviceStaging(case)
     model = oracle.Staging(numel, R, case.shard_off, case.full_off)

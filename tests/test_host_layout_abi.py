@@ -164,5 +164,5 @@ def test_probe_and_tune_argument_errors():
     assert lib.odc_tune(b"defaults", 1) == odc.ODC_ERR_INVALID_ARG
     for knob, value in [(b"gather_threads", 64), (b"accum_threads", 128), (b"reset_threads", 256),
                         (b"gather_unroll", 1), (b"accum_unroll", 2), (b"reset_unroll", 4),
-                        (b"nontemporal", 0), (b"tile_remap", 1), (b"max_grid_x", 512), (b"defaults", 0)]:
+                        (b"nontemporal", 0), (b"tile_remap", 1), (b"gather_store_sc1", 0), (b"max_grid_x", 512), (b"defaults", 0)]:
         assert lib.odc_tune(knob, value) == 0
