@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket accumulate launches with events (roofline from a separate pass)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU-baseline sample time")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (launch-bound workloads); "
+                         "the roofline figure then comes from a separate eager timing loop")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE")
     ap.add_argument("--microbatch-plan", default="config", choices=["config", "lb-mini", "lb-micro"],
                     help="config: the workload's own per-rank microbatch counts; lb-mini / lb-micro: draw a "
@@ -260,14 +263,31 @@ def main():
         run_step(L, sets, full, pool, layers, M, odc)
     torch.cuda.synchronize()
 
-    events = None if args.no_kernel_events else EventPool(torch)
-    t0 = time.perf_counter()
+    events = None if (args.no_kernel_events or args.graph) else EventPool(torch)
     n_g = n_c = n_r = 0
-    for _ in range(args.steps):
-        a, b, c = run_step(L, sets, full, pool, layers, M, odc, events)
-        n_g, n_c, n_r = n_g + a, n_c + b, n_r + c
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        # The library calls only enqueue kernels on the stream they are given (no allocation,
+        # no synchronisation, no memset), so a whole step can be captured and replayed.
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                a, b, c = run_step(L, sets, full, pool, layers, M, odc)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+            n_g, n_c, n_r = n_g + a, n_c + b, n_r + c
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            a, b, c = run_step(L, sets, full, pool, layers, M, odc, events)
+            n_g, n_c, n_r = n_g + a, n_c + b, n_r + c
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     eff_bytes = total * (4 * n_g + 10 * n_c + 4 * n_r)
     value = eff_bytes / dt / 1e9
@@ -313,6 +333,7 @@ def main():
                                "reset": n_r // args.steps},
             "bytes_rule": "4 B/elem/gather, 10 B/elem/contribution, 4 B/elem/reset",
             "tune": args.tune, "microbatch_plan": plan_info or "config",
+            "launch": "hip graph replay" if args.graph else "eager",
         },
         "roofline": {
             "bound": "hbm", "kernel": "scatter_accumulate (ordered)",

@@ -472,3 +472,70 @@ def test_staging_argument_errors():
     assert odc.stage_drain_rc(L, st.bufs, st.flags, st.snap, case.acc_ptrs) == 0
     torch.cuda.synchronize()
     case.close()
+
+
+@pytest.mark.parametrize("numel,R", [([1_048_589], 4), ([4099, 1, 70_001, 12_345, 8], 8)])
+def test_hip_graph_replay_matches_oracle(oracle, numel, R):
+    """The entry points only enqueue kernels (no allocation, memset or synchronisation), so a
+    step -- gather, reset, three ordered contributions, retrieval -- can be captured into a HIP
+    graph.  Every replay reads the buffers as they are at replay time: the inputs change between
+    replays, with eager launches and synchronisations in between, and each replay is checked
+    against the oracle."""
+    print(f"graph case R={R} numel={numel}", flush=True)
+    case = DeviceCase(R, numel)
+    L = case.layout
+    grads = [torch.zeros(case.full_n, dtype=torch.int16, device="cuda") for _ in range(3)]
+    out = [torch.zeros(case.arena, dtype=torch.float32, device="cuda") for _ in range(R)]
+    out_ptrs = odc.PtrArray(out)
+    scale = 0.25
+
+    def step():
+        L.gather(case.param_ptrs, case.full.t)
+        L.reset_accum(case.acc_ptrs)
+        for k, g in enumerate(grads):
+            L.scatter_accumulate(g, case.acc_ptrs, k, 0)
+        L.retrieve_grads(case.acc_ptrs, out_ptrs, scale, odc.ODC_OUT_F32)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+
+    for replay in range(4):
+        flats = [inputs.uniform_bf16(n, -0.05, 0.05, seed=(77, replay, t)) for t, n in enumerate(numel)]
+        arenas = host_arenas_from_flats(oracle, flats, R, case.S, case.shard_off, case.arena)
+        case.load_params(arenas)
+        g_host = [inputs.normal_bf16(case.full_n, 1e-3, seed=(78, replay, k)) for k in range(3)]
+        for g, h in zip(grads, g_host):
+            g.copy_(to_dev_u16(h))
+        # eager work between replays: dirty the outputs the replay has to rewrite
+        case.full.t[:case.full_n].fill_(0x1234)
+        L.scatter_accumulate(grads[0], case.acc_ptrs, 0, 0, odc.ODC_UNORDERED)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+
+        want_full = np.full(case.full_n, FULL16, dtype=np.uint16)
+        got_full = to_host_u16(case.full.t)
+        oracle.gather_batched(arenas, numel, case.shard_off, case.full_off, want_full)
+        for t, n in enumerate(numel):
+            a = case.full_off[t]
+            assert_bits_equal(got_full[a:a + n], want_full[a:a + n], f"replay {replay} gather tensor {t}")
+        acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+        oracle.reset_batched(acc_host, numel, case.shard_off)
+        for h in g_host:
+            oracle.accumulate_batched(h, acc_host, numel, case.shard_off, case.full_off)
+        for r, a in enumerate(case.acc_host()):
+            assert_bits_equal(a, acc_host[r], f"replay {replay} accumulate rank {r}")
+        want_out = [np.zeros(case.arena, dtype=np.float32) for _ in range(R)]
+        oracle.retrieve_batched(acc_host, want_out, numel, case.shard_off, scale=scale)
+        for r in range(R):
+            got = out[r].cpu().numpy()
+            for t in range(len(numel)):
+                a, v = case.shard_off[t], L.valid_elems(t, r)
+                assert_bits_equal(got[a:a + v], want_out[r][a:a + v], f"replay {replay} retrieve rank {r} tensor {t}")
+    case.check_guards()
+    case.close()
