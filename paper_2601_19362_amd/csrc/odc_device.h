@@ -607,7 +607,7 @@ template <bool NT>
 __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
                                                                   uint16_t *__restrict__ full, int r0, int nr)
 {
-    constexpr int UG = 2;  // items in flight per thread
+    constexpr int UG = 1;  // items in flight per thread
     static_assert(kGatherChunks % UG == 0, "tile must hold a whole number of item groups");
     __shared__ GatherTile lds;
     if (threadIdx.x < kRanksPerLaunch) lds.base[threadIdx.x] = arenas.p[threadIdx.x];
@@ -765,7 +765,10 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float w)
     }
 }
 
-// One-dimensional grid over (tile of the rank arena, group of RG owners), group fastest.
+// One-dimensional grid over (group of RG owners, tile of the rank arena), tile fastest:
+// consecutive workgroups sweep one owner group's arenas from start to end, so the chip works
+// on a few advancing address windows at a time (measurably faster than spreading every tile
+// over all owners first).
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
 __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
@@ -777,8 +780,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
     const int64_t nwork = ntiles * ngroups;
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / ngroups;
-        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
+        const int rl0 = static_cast<int>(work / ntiles) * RG;
+        const int64_t tile = work % ntiles;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
         AccumItem items[kAccumItems][RG];
@@ -814,8 +817,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / ngroups;
-        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
+        const int rl0 = static_cast<int>(work / ntiles) * RG;
+        const int64_t tile = work % ntiles;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
@@ -911,7 +914,7 @@ __global__ __launch_bounds__(64) void k_accum_multi_flat(RankPtrs accs, GradPtrs
         accum_multi_one<K, ATOMIC>(acc, grads, base, 4 * nitem + threadIdx.x);
 }
 
-// Batched form: one workgroup per (tile of the rank arena, owner), owner fastest.
+// Batched form: one workgroup per (owner, tile of the rank arena), tile fastest.
 template <int K, bool ATOMIC>
 __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTable tb, RankPtrs accs, GradPtrs grads,
                                                                        int r0, int nr)
@@ -921,8 +924,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
     const int64_t nwork = ntiles * nr;
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / nr;
-        const int rl = static_cast<int>(work - tile * nr);
+        const int rl = static_cast<int>(work / ntiles);
+        const int64_t tile = work % ntiles;
         float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1002,8 +1005,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
     const int64_t nwork = ntiles * nr;
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / nr;
-        const int rl = static_cast<int>(work - tile * nr);
+        const int rl = static_cast<int>(work / ntiles);
+        const int64_t tile = work % ntiles;
         const int r = r0 + rl;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1134,8 +1137,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
     const int64_t nwork = ntiles * nr;
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / nr;
-        const int rl = static_cast<int>(work - tile * nr);
+        const int rl = static_cast<int>(work / ntiles);
+        const int64_t tile = work % ntiles;
         const int r = r0 + rl;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1232,8 +1235,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
     const int64_t nwork = ntiles * ngroups;
     for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
         if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int64_t tile = work / ngroups;
-        const int rl0 = static_cast<int>(work - tile * ngroups) * RG;
+        const int rl0 = static_cast<int>(work / ntiles) * RG;
+        const int64_t tile = work % ntiles;
         int t_lo, n;
         stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll

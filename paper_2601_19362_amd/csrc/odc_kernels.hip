@@ -117,13 +117,14 @@ static unsigned batched_grid_x(int64_t work)
     return grid_x_for(work, 1, tuning().max_grid_x);
 }
 
-// Owners per workgroup in the batched accumulate / reset kernels: as many as still leave
-// enough workgroups to fill the chip several times over.
-static int rank_group(int64_t tiles, int nr)
+// Owners per workgroup in the batched accumulate / reset / retrieve kernels.  A workgroup that
+// serves two owners looks its tensors up once for both, which pays for the read-modify-write
+// kernels when there is enough work to fill the chip; the write-only reset is fastest with one.
+static int rank_group(int64_t tiles, int nr, int preferred)
 {
     const int forced = tuning().batch_rank_group;
     if (forced > 0) return forced;
-    for (int rg = 8; rg > 1; rg >>= 1)
+    for (int rg = preferred; rg > 1; rg >>= 1)
         if (tiles * ((nr + rg - 1) / rg) >= 4096) return rg;
     return 1;
 }
@@ -158,7 +159,7 @@ int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr);
+    const int rg = rank_group(tiles, nr, 2);
     const int64_t work = tiles * ((nr + rg - 1) / rg);
 #define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                                   \
     ODC_DISPATCH_RG(rg, NTF,                                                                                         \
@@ -177,7 +178,7 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr);
+    const int rg = rank_group(tiles, nr, 1);
     const int64_t work = tiles * ((nr + rg - 1) / rg);
     ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
                     (k_reset_batched<RG_, NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
@@ -335,7 +336,7 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
     const RankPtrs ro = pack(out, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr);
+    const int rg = rank_group(tiles, nr, 2);
     const int64_t work = tiles * ((nr + rg - 1) / rg);
     if (bf16) {
         ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
