@@ -347,7 +347,6 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
 
 constexpr int kChunkElems = 1 << kChunkShift;
 constexpr int kBatchThreads = 256;
-constexpr int kGatherChunks = 4;  // gather tile: 4 chunks = 4 items of 8 elements per thread
 constexpr int kAccumItems = kChunkElems / (4 * kBatchThreads);  // accumulate tile: 1 chunk
 
 template <int CHUNKS>
@@ -403,32 +402,30 @@ __device__ __forceinline__ int valid_from(const TensorDesc &d, int r, int64_t sl
 }
 
 // ---- gather, full-buffer-major ---------------------------------------------------------
-// Per-tensor record of the gather kernel, staged in LDS for multi-tensor tiles.  Offsets are
-// 32-bit and relative to the tile so that the per-item index arithmetic stays in 32-bit
-// integer instructions (64-bit vector integer math is several times slower on this chip
-// and used to make this kernel ALU-bound).  Tensors of 2^30 elements or more take a generic
-// 64-bit path instead (S = 0 marks them).
+// Per-tensor record of the gather kernel, staged in LDS once per tile.  Offsets are 32-bit
+// and relative to the tile so that the per-item index arithmetic stays in 32-bit integer
+// instructions (64-bit vector integer math is several times slower on this chip and used to
+// make this kernel ALU-bound).  Tensors of 2^30 elements or more take a generic 64-bit path
+// instead (S = 0 marks them).
 struct GatherRec {
     int32_t rel;        // full_off - tile start (may be negative: tensor began before the tile)
     uint32_t S;         // shard elements; 0 = use the generic path
     uint32_t numel;
     int64_t shard_off;  // start inside every rank arena
-    int32_t tensor;     // index into the descriptor table (generic path)
 };
 
-__device__ __forceinline__ GatherRec make_gather_rec(const TensorDesc &d, int tensor, int64_t a0)
+__device__ __forceinline__ GatherRec make_gather_rec(const TensorDesc &d, int64_t a0)
 {
     GatherRec g;
     const int64_t lim = int64_t{1} << 30;
     const int64_t rel = d.full_off - a0;
     // A tensor that intersects the tile began less than numel elements before it, so a
     // small tensor's offset always fits; only the ordering matters for the others.
-    const bool small = d.numel < lim && rel > -lim;
+    const bool small = d.numel < (int64_t{1} << kGatherSmallShift);
     g.rel = static_cast<int32_t>(rel < -lim ? -lim : (rel > lim ? lim : rel));
     g.S = small ? static_cast<uint32_t>(d.S) : 0u;
     g.numel = small ? static_cast<uint32_t>(d.numel) : 0u;
     g.shard_off = d.shard_off;
-    g.tensor = tensor;
     return g;
 }
 
@@ -453,60 +450,49 @@ __device__ __forceinline__ uint32_t div_owner(uint32_t j, uint32_t S)
     return r;
 }
 
-// Elements of one item that do not all sit in one owner's shard (small tensors, shard
-// boundaries, ragged tensor ends): all element loads first, then one wide store if the item
-// is complete and wholly served by this launch, else element stores.
-template <bool NT>
-__device__ __forceinline__ void gather_pieces(uint32_t r, uint32_t i, uint32_t S, int64_t shard_off, int cnt,
-                                              void *const *base, int r0, int nr, uint16_t *dst)
+// The same for 64-bit operands (0 <= j < 2^62, quotient below 2^12): the conversions, the
+// reciprocal and the product are each good to about 2^-23, so the estimate is within
+// 2^12 * 2^-21 < 1 of the quotient and one step of repair is enough.  Replaces a 64-bit
+// integer division, which the compiler expands into a long instruction sequence.
+__device__ __forceinline__ int64_t div_owner64(int64_t j, int64_t S)
 {
-    uint32_t e[8];
-    bool mine = true;
-    uint32_t rr = r, ii = i;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        e[k] = 0;
-        if (k < cnt) {
-            const bool in = rr >= static_cast<uint32_t>(r0) && rr < static_cast<uint32_t>(r0 + nr);
-            mine = mine && in;
-            if (in) e[k] = ld_u16(static_cast<const uint16_t *>(base[rr - r0]) + shard_off + ii);
-            if (++ii == S) {
-                ii = 0;
-                ++rr;
-            }
-        }
-    }
-    if (cnt == 8 && mine) {
-        const u32x4 v = {e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-        st<NT>(reinterpret_cast<u32x4 *>(dst), v);
-        return;
-    }
-    rr = r;
-    ii = i;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        if (k < cnt) {
-            if (rr >= static_cast<uint32_t>(r0) && rr < static_cast<uint32_t>(r0 + nr))
-                st_u16(dst + k, static_cast<uint16_t>(e[k]));
-            if (++ii == S) {
-                ii = 0;
-                ++rr;
-            }
+    int64_t r = static_cast<int64_t>(static_cast<float>(j) * fast_rcp(static_cast<float>(S)));
+    const int64_t i = j - r * S;
+    if (i < 0) --r;
+    else if (i >= S) ++r;
+    return r;
+}
+
+// One item copied element by element, each element from whichever owner holds it; owners
+// outside this launch are left to the launch that serves them.  Sequential on purpose (few
+// registers): used only where a wide load could run past the end of an arena.
+__device__ __forceinline__ void gather_elements(uint32_t j, uint32_t S, int64_t shard_off, int cnt,
+                                                void *const *base, int r0, int nr, uint16_t *dst)
+{
+    uint32_t r = div_owner(j, S);
+    uint32_t i = j - r * S;
+#pragma unroll 1
+    for (int e = 0; e < cnt; ++e) {
+        const uint32_t rl = r - static_cast<uint32_t>(r0);
+        if (rl < static_cast<uint32_t>(nr))
+            st_u16(dst + e, ld_u16(static_cast<const uint16_t *>(base[rl]) + shard_off + i));
+        if (++i == S) {
+            i = 0;
+            ++r;
         }
     }
 }
 
-// Generic 64-bit form of one item, for tensors too large for the 32-bit records.
+// Generic 64-bit form of one item, for tensors too large for the 32-bit records (their
+// shards are far longer than an item, so an item touches at most two owners).
 template <bool NT>
 __device__ __forceinline__ void gather_item_generic(const TensorDesc &d, int64_t a, void *const *base, int r0,
                                                     int nr, uint16_t *dst)
 {
     const int64_t j = a - d.full_off;
-    if (j >= d.numel) return;
+    if (j < 0 || j >= d.numel) return;
     const int cnt = d.numel - j >= 8 ? 8 : static_cast<int>(d.numel - j);
-    int64_t r = ((static_cast<uint64_t>(j) | static_cast<uint64_t>(d.S)) >> 32)
-                    ? j / d.S
-                    : static_cast<int64_t>(static_cast<uint32_t>(j) / static_cast<uint32_t>(d.S));
+    int64_t r = div_owner64(j, d.S);
     int64_t i = j - r * d.S;
     if (cnt == 8 && i + 8 <= d.S) {
         if (r >= r0 && r < r0 + nr)
@@ -514,6 +500,7 @@ __device__ __forceinline__ void gather_item_generic(const TensorDesc &d, int64_t
                    ld_u128_unaligned<NT>(static_cast<const uint16_t *>(base[r - r0]) + d.shard_off + i));
         return;
     }
+#pragma unroll 1
     for (int k = 0; k < cnt; ++k) {  // at most one such item per shard boundary
         if (r >= r0 && r < r0 + nr)
             st_u16(dst + k, ld_u16(static_cast<const uint16_t *>(base[r - r0]) + d.shard_off + i));
@@ -550,68 +537,54 @@ __device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, int k)
 }
 
 constexpr int kGatherMaxTensors = kGatherChunks * kMaxTensorsPerChunk + 2;
+constexpr int kGatherFewTensors = 32;  // LDS capacity of the variant for ordinary layouts
 
+template <int CAP>
 struct GatherTile {
-    int32_t rel[kGatherMaxTensors];
-    uint32_t S[kGatherMaxTensors];
-    uint32_t numel[kGatherMaxTensors];
-    int64_t shard_off[kGatherMaxTensors];
+    int32_t rel[CAP];
+    uint32_t S[CAP];
+    uint32_t numel[CAP];
+    int64_t shard_off[CAP];
     void *base[kRanksPerLaunch];
 };
 
-// Where one 8-element item of the full buffer comes from.
-struct GatherLoc {
-    int64_t shard_off;
-    uint32_t S;       // 0: tensor needs the generic 64-bit path
-    uint32_t r, i;    // owner and slot of the item's first element
-    int cnt;          // valid elements: 0 (gap), 1..8
-    int k;            // staged tensor index within the tile
-};
+// What pass 1 of the gather kernel leaves for pass 2, packed into one register per item:
+// kind in bits 0..3, then three 4-bit element counts.
+enum : int { kGatherNone = 0, kGatherWide = 1, kGatherGeneric = 2, kGatherElements = 3 };
 
-__device__ __forceinline__ GatherLoc gather_locate(const GatherTile &lds, const GatherRec &one, int n, int a_rel)
+// Index of the staged tensor that holds tile-relative element a_rel.
+template <int CAP>
+__device__ __forceinline__ int gather_find(const GatherTile<CAP> &lds, int n, int a_rel)
 {
-    GatherLoc L;
-    int32_t rel = one.rel;
-    uint32_t numel = one.numel;
-    L.S = one.S;
-    L.shard_off = one.shard_off;
-    L.k = 0;
-    if (n > 1) {
-        int lo = 0, hi = n - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (lds.rel[mid] <= a_rel) lo = mid;
-            else hi = mid - 1;
-        }
-        L.k = lo;
-        rel = lds.rel[lo];
-        L.S = lds.S[lo];
-        numel = lds.numel[lo];
-        L.shard_off = lds.shard_off[lo];
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (lds.rel[mid] <= a_rel) lo = mid;
+        else hi = mid - 1;
     }
-    L.r = L.i = 0;
-    L.cnt = 0;
-    if (L.S == 0) return L;
-    const uint32_t j = static_cast<uint32_t>(a_rel - rel);
-    if (j >= numel) return L;  // alignment gap after the tensor
-    L.r = div_owner(j, L.S);
-    L.i = j - L.r * L.S;
-    L.cnt = numel - j >= 8 ? 8 : static_cast<int>(numel - j);
-    return L;
+    return lo;
 }
 
 // grid.x = tiles of the full buffer; owners [r0, r0 + nr) are served by this launch.
-// A tile is kGatherChunks chunks; each thread handles its items two at a time: both items'
-// wide loads are issued before either is stored.
-template <bool NT>
+//
+// A tile is kGatherChunks chunks, i.e. kGatherChunks items of 8 elements per thread, taken
+// UG at a time: pass 1 locates the items and issues their wide loads, pass 2 stores.  An
+// item of a tensor with S >= 8 lies in one owner's shard or straddles into the next owner's:
+// one or two wide loads (the first may run past the end of the shard piece into the owner's
+// next slots, which are inside the arena unless the item is the arena's last) and, for a
+// straddling item, a splice.  When one of the two owners belongs to another launch only the
+// elements of the owner served here are stored.  The kernel is deliberately lean: it runs
+// at the rate the number of resident wavefronts allows, so everything rare is kept out of
+// the main path -- tensors with S < 8 (an item spans three or more owners) are skipped here
+// and copied element-wise, one lane per element, by the loop at the end of the kernel.
+template <bool NT, int CAP>
 __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
                                                                   uint16_t *__restrict__ full, int r0, int nr)
 {
-    constexpr int UG = 1;  // items in flight per thread
+    constexpr int UG = 2;  // items in flight per thread
     static_assert(kGatherChunks % UG == 0, "tile must hold a whole number of item groups");
-    __shared__ GatherTile lds;
+    __shared__ GatherTile<CAP> lds;
     if (threadIdx.x < kRanksPerLaunch) lds.base[threadIdx.x] = arenas.p[threadIdx.x];
-    __syncthreads();
     const int64_t nchunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t ntiles = (nchunks + kGatherChunks - 1) / kGatherChunks;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
@@ -620,86 +593,104 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
         const int64_t c1 = c0 + kGatherChunks < nchunks ? c0 + kGatherChunks : nchunks;
         const int64_t a0 = c0 << kChunkShift;
         const int t_lo = tb.full_chunk_first[c0];
-        const int n = tb.full_chunk_first[c1] - t_lo + 1;
-        GatherRec one{};
-        if (n == 1) {
-            one = make_gather_rec(tb.desc[t_lo], t_lo, a0);
-        } else {
-            for (int k = threadIdx.x; k < n; k += kBatchThreads) {
-                const GatherRec g = make_gather_rec(tb.desc[t_lo + k], t_lo + k, a0);
-                lds.rel[k] = g.rel;
-                lds.S[k] = g.S;
-                lds.numel[k] = g.numel;
-                lds.shard_off[k] = g.shard_off;
-            }
-            __syncthreads();
+        const int n = tb.full_chunk_first[c1] - t_lo + 1;  // <= CAP: the launcher picked CAP
+        for (int k = threadIdx.x; k < n; k += kBatchThreads) {
+            const GatherRec g = make_gather_rec(tb.desc[t_lo + k], a0);
+            lds.rel[k] = g.rel;
+            lds.S[k] = g.S;
+            lds.numel[k] = g.numel;
+            lds.shard_off[k] = g.shard_off;
         }
+        __syncthreads();
         const int64_t tile_elems = tb.full_elems - a0;  // elements from the tile start to the buffer end
 
 #pragma unroll 1
         for (int grp = 0; grp < kGatherChunks / UG; ++grp) {
-            // pass 1: locate the items and issue their wide loads.  An item of a tensor with
-            // S >= 8 lies in one owner's shard or straddles into the next owner's: one or
-            // two wide loads (the first may run past the end of the shard piece into the
-            // owner's next slots, hence `room`).  Everything else -- tensors with S < 8,
-            // owners outside this launch, the very end of an arena, huge tensors -- is
-            // finished element by element in pass 2.
-            u32x4 ra[UG], rb[UG];
-            int kind[UG];   // 0 nothing, 1 wide (spliced with rb if split > 0), 2 the rest
-            int split[UG];  // elements taken from the first owner when the item straddles
-            int cnt[UG];
+            u32x4 va[UG], vb[UG];
+            int code[UG];
 #pragma unroll
             for (int u = 0; u < UG; ++u) {
-                kind[u] = 0;
-                split[u] = 0;
-                cnt[u] = 0;
+                code[u] = kGatherNone;
+                va[u] = u32x4{0u, 0u, 0u, 0u};
+                vb[u] = va[u];
                 const int a_rel = 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x));
                 if (a_rel >= tile_elems) continue;
-                const GatherLoc L = gather_locate(lds, one, n, a_rel);
-                if (L.S == 0) {
-                    kind[u] = 2;
+                const int k = gather_find(lds, n, a_rel);
+                const uint32_t S = lds.S[k];
+                if (S == 0) {
+                    code[u] = kGatherGeneric;
                     continue;
                 }
-                if (L.cnt == 0) continue;
-                cnt[u] = L.cnt;
-                const uint32_t rl = L.r - static_cast<uint32_t>(r0);  // huge if r < r0
-                const bool straddles = L.i + static_cast<uint32_t>(L.cnt) > L.S;
-                const bool room = L.shard_off + L.i + 8 <= tb.arena_elems;
-                if (L.S >= 8 && room && rl < static_cast<uint32_t>(nr) &&
-                    (!straddles || rl + 1 < static_cast<uint32_t>(nr))) {
-                    kind[u] = 1;
-                    ra[u] = ld_u128_unaligned<NT>(static_cast<const uint16_t *>(lds.base[rl]) + L.shard_off + L.i);
-                    if (straddles) {
-                        split[u] = static_cast<int>(L.S - L.i);
-                        rb[u] = ld<NT>(reinterpret_cast<const u32x4 *>(
-                            static_cast<const uint16_t *>(lds.base[rl + 1]) + L.shard_off));
-                    }
-                } else {
-                    kind[u] = 2;
+                const uint32_t j = static_cast<uint32_t>(a_rel - lds.rel[k]);
+                const uint32_t numel = lds.numel[k];
+                if (S < 8 || j >= numel) continue;  // element-wise loop below / alignment gap
+                const uint32_t cnt = numel - j >= 8 ? 8u : numel - j;
+                const uint32_t r = div_owner(j, S);
+                const uint32_t i = j - r * S;
+                const uint32_t rl = r - static_cast<uint32_t>(r0);  // wraps if r < r0
+                const uint32_t split = i + cnt > S ? S - i : 0u;    // elements from the first owner if two
+                const bool in_a = rl < static_cast<uint32_t>(nr);
+                const bool in_b = split != 0 && rl + 1 < static_cast<uint32_t>(nr);
+                if (!in_a && !in_b) continue;
+                const int64_t shard_off = lds.shard_off[k];
+                if (in_a && shard_off + i + 8 > tb.arena_elems) {
+                    code[u] = kGatherElements;
+                    continue;
                 }
+                const uint32_t e_lo = in_a ? 0u : split;
+                const uint32_t e_hi = (split != 0 && !in_b) ? split : cnt;
+                if (in_a) va[u] = ld_u128_unaligned<NT>(static_cast<const uint16_t *>(lds.base[rl]) + shard_off + i);
+                if (in_b)
+                    vb[u] = ld<NT>(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(lds.base[rl + 1]) +
+                                                                   shard_off));
+                code[u] = kGatherWide | static_cast<int>(split << 4 | e_lo << 8 | e_hi << 12);
             }
-            // pass 2: aligned wide stores; the rarer kinds are located again and finished
 #pragma unroll
             for (int u = 0; u < UG; ++u) {
+                const int kind = code[u] & 15;
+                if (kind == kGatherNone) continue;
                 const int a_rel = 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x));
                 uint16_t *dst = full + a0 + a_rel;
-                if (kind[u] == 1) {
-                    u32x4 v = ra[u];
-                    if (split[u] > 0) v = splice(ra[u], rb[u], split[u]);
-                    if (cnt[u] == 8) {
+                if (kind == kGatherWide) {
+                    const int split = (code[u] >> 4) & 15, e_lo = (code[u] >> 8) & 15, e_hi = (code[u] >> 12) & 15;
+                    const u32x4 v = split ? splice(va[u], vb[u], split) : va[u];
+                    if (e_lo == 0 && e_hi == 8) {
                         st<NT>(reinterpret_cast<u32x4 *>(dst), v);
-                    } else {  // ragged end of the tensor: the slots after it are never written
+                    } else {  // ragged tensor end, or an owner of another launch: its slots stay untouched
                         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                        for (int e = 0; e < 7; ++e)
-                            if (e < cnt[u]) st_u16(dst + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
+                        for (int e = 0; e < 8; ++e)
+                            if (e >= e_lo && e < e_hi) st_u16(dst + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
                     }
-                } else if (kind[u] == 2) {
-                    const GatherLoc L = gather_locate(lds, one, n, a_rel);
-                    if (L.S == 0) gather_item_generic<NT>(tb.desc[t_lo + L.k], a0 + a_rel, lds.base, r0, nr, dst);
-                    else gather_pieces<NT>(L.r, L.i, L.S, L.shard_off, L.cnt, lds.base, r0, nr, dst);
+                } else {  // rare: located again rather than kept in registers
+                    const int k = gather_find(lds, n, a_rel);
+                    if (kind == kGatherGeneric) {
+                        gather_item_generic<NT>(tb.desc[t_lo + k], a0 + a_rel, lds.base, r0, nr, dst);
+                    } else {
+                        const uint32_t j = static_cast<uint32_t>(a_rel - lds.rel[k]);
+                        const uint32_t numel = lds.numel[k];
+                        gather_elements(j, lds.S[k], lds.shard_off[k], numel - j >= 8 ? 8 : static_cast<int>(numel - j),
+                                        lds.base, r0, nr, dst);
+                    }
                 }
             }
+        }
+    }
+
+    // Tensors with S < 8: one wavefront per tensor, one lane per element.
+    __syncthreads();  // lds.base is visible even to a workgroup that had no tile
+    const int wave = static_cast<int>(threadIdx.x) >> 6, lane = static_cast<int>(threadIdx.x) & 63;
+    constexpr int kWaves = kBatchThreads / 64;
+    for (int64_t s = static_cast<int64_t>(blockIdx.x) * kWaves + wave; s < tb.n_spread;
+         s += static_cast<int64_t>(gridDim.x) * kWaves) {
+        const TensorDesc d = tb.desc[tb.spread[s]];
+        const uint32_t S = static_cast<uint32_t>(d.S), numel = static_cast<uint32_t>(d.numel);
+        for (uint32_t j = static_cast<uint32_t>(lane); j < numel; j += 64) {
+            const uint32_t r = div_owner(j, S);
+            const uint32_t rl = r - static_cast<uint32_t>(r0);
+            if (rl < static_cast<uint32_t>(nr))
+                st_u16(full + d.full_off + j,
+                       ld_u16(static_cast<const uint16_t *>(lds.base[rl]) + d.shard_off + (j - r * S)));
         }
     }
 }

@@ -18,6 +18,16 @@ constexpr int64_t kAlignElems = 8;
 // Rank-arena elements per entry of the coarse tensor-lookup index (power of two).
 constexpr int kChunkShift = 11;
 
+// The batched gather kernel works on tiles of this many chunks of the full buffer.
+constexpr int kGatherChunks = 4;
+// Tensors below 2^kGatherSmallShift elements use 32-bit tile-relative index arithmetic in
+// the batched gather kernel, larger ones a 64-bit path.  (A build of the CPU emulation lowers
+// the limit so that small test cases reach the 64-bit path.)
+#ifndef ODC_GATHER_SMALL_SHIFT
+#define ODC_GATHER_SMALL_SHIFT 30
+#endif
+constexpr int kGatherSmallShift = ODC_GATHER_SMALL_SHIFT;
+
 // Per-tensor record read by the batched kernels.
 struct TensorDesc {
     int64_t shard_off;  // start inside every rank arena (elements)
@@ -32,9 +42,13 @@ struct BatchTable {
     const int32_t *chunk_first;       // rank-arena space, [arena tiles + 1]: last tensor whose
                                       // shard_off is at or before the tile's first element
     const int32_t *full_chunk_first;  // the same for the full buffer (full_off)
+    const int32_t *spread;            // [n_spread]: tensors with S < 8 (an 8-element item of
+                                      // theirs is spread over more than two owners)
     int64_t arena_elems;
     int64_t full_elems;
     int32_t T;
+    int32_t n_spread;
+    int32_t gather_tile_tensors;      // most tensors that intersect one gather tile
 };
 
 struct HostLayout {
@@ -46,6 +60,8 @@ struct HostLayout {
     int64_t total_numel = 0;
     std::vector<int32_t> chunk_first;       // built for T > 1
     std::vector<int32_t> full_chunk_first;  // built for T > 1
+    std::vector<int32_t> spread;            // built for T > 1: tensors with S < kAlignElems
+    int gather_tile_tensors = 1;            // built for T > 1
 };
 
 // Pure integer layout construction (Section 3.1 even partition, tail padding).

@@ -146,9 +146,15 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                    (k_gather_batched<NT_><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
-                        tb, rp, static_cast<uint16_t *>(full), r0, nr)));
+    if (tb.gather_tile_tensors <= kGatherFewTensors) {
+        ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                        (k_gather_batched<NT_, kGatherFewTensors><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
+                            tb, rp, static_cast<uint16_t *>(full), r0, nr)));
+    } else {
+        ODC_DISPATCH_NT(tuning().nontemporal != 0,
+                        (k_gather_batched<NT_, kGatherMaxTensors><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
+                            tb, rp, static_cast<uint16_t *>(full), r0, nr)));
+    }
     return finish();
 }
 

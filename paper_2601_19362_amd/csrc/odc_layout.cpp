@@ -90,6 +90,24 @@ int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out)
             }
         }
     }
+    if (T > 1) {
+        // What the batched gather kernel needs beyond the indices: the tensors it copies
+        // element-wise, and the most tensors any of its tiles holds (sizes its LDS staging).
+        try {
+            for (int t = 0; t < T; ++t)
+                if (L.desc[static_cast<size_t>(t)].S < kAlignElems) L.spread.push_back(t);
+        } catch (...) {
+            return ODC_ERR_NOMEM;
+        }
+        const int64_t n_chunks = static_cast<int64_t>(L.full_chunk_first.size()) - 1;
+        int most = 1;
+        for (int64_t c0 = 0; c0 < n_chunks; c0 += kGatherChunks) {
+            const int64_t c1 = c0 + kGatherChunks < n_chunks ? c0 + kGatherChunks : n_chunks;
+            const int n = L.full_chunk_first[static_cast<size_t>(c1)] - L.full_chunk_first[static_cast<size_t>(c0)] + 1;
+            if (n > most) most = n;
+        }
+        L.gather_tile_tensors = most;
+    }
     *out = std::move(L);
     return ODC_OK;
 }

@@ -142,6 +142,7 @@ int main(int argc, char **argv)
     const std::string dir = argv[1], op = argv[2];
     const int R = std::atoi(argv[3]);
     int threads = 256, unroll = 4, nt = 1, remap = 0, atomic = 0, cap = 0, rg = 1, weighted = 0, bf16 = 0, count = 2;
+    int lds_max = 0;  // 1: use the large-LDS gather variant even where the small one would do
     float weight = 1.0f, scale = 1.0f;
     std::string script;
     for (int k = 4; k < argc; ++k) {
@@ -159,6 +160,7 @@ int main(int argc, char **argv)
         else if (key == "weighted") weighted = std::atoi(val.c_str());
         else if (key == "bf16") bf16 = std::atoi(val.c_str());
         else if (key == "count") count = std::atoi(val.c_str());
+        else if (key == "lds_max") lds_max = std::atoi(val.c_str());
         else if (key == "script") script = val;
         else if (key == "weight") weight = std::strtof(val.c_str(), nullptr);
         else if (key == "scale") scale = std::strtof(val.c_str(), nullptr);
@@ -177,7 +179,8 @@ int main(int argc, char **argv)
         return 3;
     }
     const size_t arena = static_cast<size_t>(H.arena_elems), full_n = static_cast<size_t>(H.full_elems);
-    BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.arena_elems, H.full_elems, H.T};
+    BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.spread.data(), H.arena_elems,
+                  H.full_elems, H.T, static_cast<int32_t>(H.spread.size()), H.gather_tile_tensors};
     const bool flat = H.T == 1;
     const int64_t S = H.desc[0].S, N = H.desc[0].numel;
 
@@ -206,8 +209,15 @@ int main(int argc, char **argv)
             } else {
                 const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
                 const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
-                EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap),
-                                             [&] { k_gather_batched<NT_>(tb, rp, full, r0, nr); }));
+                if (tb.gather_tile_tensors <= kGatherFewTensors && !lds_max) {
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), [&] {
+                               k_gather_batched<NT_, kGatherFewTensors>(tb, rp, full, r0, nr);
+                           }));
+                } else {
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), [&] {
+                               k_gather_batched<NT_, kGatherMaxTensors>(tb, rp, full, r0, nr);
+                           }));
+                }
             }
         }
         write_file(dir + "/full.out", full, full_n);
@@ -216,6 +226,7 @@ int main(int argc, char **argv)
         return 0;
     }
 
+#ifndef EMU_GATHER_ONLY  // a build that only needs the gather kernels compiles much faster
     if (op == "accum" || op == "reset") {
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;
@@ -470,6 +481,7 @@ int main(int argc, char **argv)
         for (auto *b : outs) std::free(b);
         return 0;
     }
+#endif  // EMU_GATHER_ONLY
 
     std::fprintf(stderr, "unknown op %s\n", op.c_str());
     return 2;

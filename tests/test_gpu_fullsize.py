@@ -184,3 +184,51 @@ def test_32b_rotating_window(oracle):
                                       f"layer {layer} accumulate rank {r} [{lo},{hi})")
         del flat, grads
     L.close()
+
+
+def test_multi_tensor_layout_with_a_2p30_element_tensor(oracle):
+    """A multi-tensor layout whose first tensor has more than 2^30 elements: the batched gather
+    kernel leaves its 32-bit tile-relative arithmetic for such a tensor, and every batched
+    kernel has to carry 64-bit offsets.  Gather, reset and two ordered contributions, compared
+    in full with the oracle."""
+    numel = [(1 << 30) + 5, 1000, 7, 70_001]
+    R = 8
+    print(f"huge-tensor case numel={numel} R={R}", flush=True)
+    L = odc.Layout(R, numel)
+    T = len(numel)
+    S = [L.shard_elems(t) for t in range(T)]
+    so = [L.shard_offset(t) for t in range(T)]
+    fo = [L.full_offset(t) for t in range(T)]
+    arena, full_n = L.rank_arena_elems(), L.full_elems()
+    dev = torch.device("cuda")
+    params = [torch.full((arena,), -1.0, dtype=torch.bfloat16, device=dev) for _ in range(R)]
+    for t, n in enumerate(numel):
+        flat = inputs.device_uniform_bf16(n, -0.05, 0.05, 300 + t, dev)
+        for r in range(R):
+            v = L.valid_elems(t, r)
+            if v:
+                params[r][so[t]:so[t] + v] = flat[r * S[t]:r * S[t] + v]
+        del flat
+    full = torch.full((full_n,), 7.0, dtype=torch.bfloat16, device=dev)
+    L.gather(params, full)
+    torch.cuda.synchronize()
+    arenas_h = [p.view(torch.int16).cpu().numpy().view(np.uint16) for p in params]
+    want = np.full(full_n, 0x40E0, dtype=np.uint16)   # bf16(7.0) where nothing is written
+    oracle.gather_batched(arenas_h, numel, so, fo, want)
+    got = full.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert_bits_equal(got, want, "gather")
+    del params, arenas_h, full, got, want
+
+    acc = [torch.full((arena,), 3.25, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc_h = [np.full(arena, 3.25, dtype=np.float32) for _ in range(R)]
+    L.reset_accum(acc)
+    oracle.reset_batched(acc_h, numel, so)
+    for k in range(2):
+        g = inputs.device_normal_bf16(full_n, 1e-3, 400 + k, dev)
+        L.scatter_accumulate(g, acc, k, 0)
+        oracle.accumulate_batched(g.view(torch.int16).cpu().numpy().view(np.uint16), acc_h, numel, so, fo)
+        del g
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"accumulate rank {r}")
+    L.close()

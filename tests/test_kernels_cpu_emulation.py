@@ -22,15 +22,37 @@ PAD32 = np.float32(-12345.678)
 pytestmark = pytest.mark.skipif(not os.path.exists(CLANG), reason="ROCm clang++ not present")
 
 
+def start_build(exe, *defines):
+    return subprocess.Popen([CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                             "-fno-sanitize-recover=all", "-ffp-contract=off", "-pthread", *defines,
+                             os.path.join(ROOT, "tests", "cpu_emu", "emu_main.cpp"),
+                             os.path.join(ROOT, "paper_2601_19362_amd", "csrc", "odc_layout.cpp"),
+                             "-o", exe])
+
+
 @pytest.fixture(scope="module")
-def emu(tmp_path_factory):
-    exe = str(tmp_path_factory.mktemp("emu") / "emu")
-    subprocess.run([CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
-                    "-fno-sanitize-recover=all", "-ffp-contract=off", "-pthread",
-                    os.path.join(ROOT, "tests", "cpu_emu", "emu_main.cpp"),
-                    os.path.join(ROOT, "paper_2601_19362_amd", "csrc", "odc_layout.cpp"),
-                    "-o", exe], check=True)
-    return exe
+def emu_builds(tmp_path_factory):
+    """Both emulation binaries, compiled side by side (each takes a minute or more).  The second
+    has the size limit of the 32-bit gather records lowered from 2^30 to 2^9 elements, so that
+    ordinary test tensors take the 64-bit path meant for huge ones; it holds the gather
+    kernels only."""
+    d = tmp_path_factory.mktemp("emu")
+    exes = {"default": str(d / "emu"), "low_limit": str(d / "emu_low")}
+    procs = [start_build(exes["default"]),
+             start_build(exes["low_limit"], "-DODC_GATHER_SMALL_SHIFT=9", "-DEMU_GATHER_ONLY")]
+    for p in procs:
+        assert p.wait() == 0, "emulation build failed"
+    return exes
+
+
+@pytest.fixture(scope="module")
+def emu(emu_builds):
+    return emu_builds["default"]
+
+
+@pytest.fixture(scope="module")
+def emu_low_limit(emu_builds):
+    return emu_builds["low_limit"]
 
 
 def placement(numel, R):
@@ -76,6 +98,8 @@ CASES = [
     ([2047, 2049, 1, 4096, 8, 16384 + 7, 5], 3),  # tensors ending at, before and after tile edges
     ([129] * 40 + [70000], 66),       # batched with more than 64 ranks
     ([1] * 1100 + [20000, 2], 2),     # a gather tile whose LDS index is filled to the brim
+    ([1300, 2000, 1043, 520, 8 * 130], 130),  # S = 10, 16, 9, 4, 8 over three launch groups: items
+                                              # that straddle two owners of different launches
 ]
 
 
@@ -94,6 +118,22 @@ def test_emulated_gather(oracle, emu, tmp_path, numel, R, threads, unroll, nt, r
     assert np.array_equal(got, want)
     for t, n in enumerate(numel):
         assert np.array_equal(got[fo[t]:fo[t] + n], flats[t])
+
+
+@pytest.mark.parametrize("numel,R", CASES)
+@pytest.mark.parametrize("nt,cap,lds_max", [(1, 0, 0), (0, 2, 1)])
+def test_emulated_gather_64bit_path_and_large_lds(oracle, emu_low_limit, tmp_path, numel, R, nt, cap, lds_max):
+    """Tensors of 512 elements or more go through the 64-bit item path in this build; lds_max = 1
+    also forces the kernel variant with the full-size LDS index."""
+    S, so, fo, arena, full_n, arenas, flats = make_case(oracle, numel, R, seed=3)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    np.concatenate(arenas).tofile(tmp_path / "arenas.u16")
+    np.full(full_n, 0xBEEF, dtype=np.uint16).tofile(tmp_path / "full.u16")
+    run(emu_low_limit, tmp_path, "gather", R, nt=nt, cap=cap, lds_max=lds_max)
+    got = np.fromfile(tmp_path / "full.out", dtype=np.uint16)
+    want = np.full(full_n, 0xBEEF, dtype=np.uint16)
+    oracle.gather_batched(arenas, numel, so, fo, want)
+    assert np.array_equal(got, want)
 
 
 @pytest.mark.parametrize("numel,R", CASES)
