@@ -340,9 +340,8 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
 //   gather walks the full buffer (again the side that is written) and pulls each 16-byte
 //     item from the owner that holds it, so the pieces of a small tensor that come from
 //     many owners still leave as full 16-byte stores of one workgroup.
-// The start offsets of the tensors that intersect a tile are staged in LDS once per
-// workgroup (found through the coarse per-chunk index); each work item then locates its
-// tensor with a binary search in LDS and reads the descriptor from the L2-resident table.
+// The tensors that intersect a tile are staged in LDS once per workgroup (found through the
+// coarse per-chunk index): start offsets for a binary search, and the descriptors themselves.
 // A tile that lies inside one tensor skips all of that.
 
 constexpr int kChunkElems = 1 << kChunkShift;
@@ -352,44 +351,45 @@ constexpr int kAccumItems = kChunkElems / (4 * kBatchThreads);  // accumulate ti
 template <int CHUNKS>
 struct TileIndex {
     static constexpr int kMax = CHUNKS * (kChunkElems / static_cast<int>(kAlignElems)) + 2;
-    int32_t rel[kMax];  // start of each staged tensor relative to the tile start, clamped
-    int t_lo;
-    int n;
+    int32_t rel[kMax];      // start of each staged tensor relative to the tile start, clamped
+    TensorDesc desc[kMax];  // its descriptor, so that an item needs no second trip to memory
 };
 
-// Stage the start offsets of the tensors that intersect tile `tile` (CHUNKS chunks) of the
-// rank-arena space (FULL_SPACE = false) or of the full-buffer space (true).  All threads of
-// the workgroup must call it; it ends with a barrier unless only one tensor is involved.
-template <bool FULL_SPACE, int CHUNKS>
+// Stage the tensors that intersect tile `tile` (CHUNKS chunks) of the rank-arena space.  All
+// threads of the workgroup must call it; it ends with a barrier unless only one tensor is
+// involved (then the descriptor is read straight from the table, uniformly).
+template <int CHUNKS>
 __device__ __forceinline__ void stage_tile(const BatchTable &tb, int64_t tile, int64_t nchunks,
                                            TileIndex<CHUNKS> &lds, int &t_lo, int &n)
 {
-    const int32_t *first = FULL_SPACE ? tb.full_chunk_first : tb.chunk_first;
     const int64_t c0 = tile * CHUNKS;
     const int64_t c1 = c0 + CHUNKS < nchunks ? c0 + CHUNKS : nchunks;
-    t_lo = first[c0];
-    n = first[c1] - t_lo + 1;
+    t_lo = tb.chunk_first[c0];
+    n = tb.chunk_first[c1] - t_lo + 1;
     if (n == 1) return;
     const int64_t a0 = c0 << kChunkShift;
     for (int k = threadIdx.x; k < n; k += kBatchThreads) {
-        const TensorDesc &d = tb.desc[t_lo + k];
-        const int64_t rel = (FULL_SPACE ? d.full_off : d.shard_off) - a0;
+        const TensorDesc d = tb.desc[t_lo + k];
+        const int64_t rel = d.shard_off - a0;
         lds.rel[k] = rel < -0x40000000 ? -0x40000000 : (rel > 0x40000000 ? 0x40000000 : static_cast<int32_t>(rel));
+        lds.desc[k] = d;
     }
     __syncthreads();
 }
 
-// Index of the tensor that owns tile-relative element `a_rel`.
+// Descriptor of the tensor that owns tile-relative element `a_rel`.
 template <int CHUNKS>
-__device__ __forceinline__ int tile_tensor(int t_lo, int n, int a_rel, const TileIndex<CHUNKS> &lds)
+__device__ __forceinline__ TensorDesc tile_desc(const BatchTable &tb, int t_lo, int n, int a_rel,
+                                                const TileIndex<CHUNKS> &lds)
 {
+    if (n == 1) return tb.desc[t_lo];
     int lo = 0, hi = n - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (lds.rel[mid] <= a_rel) lo = mid;
         else hi = mid - 1;
     }
-    return t_lo + lo;
+    return lds.desc[lo];
 }
 
 // Valid elements of tensor d, owner r, starting at slot `slot`, at most `width`.
@@ -774,7 +774,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
         const int rl0 = static_cast<int>(work / ntiles) * RG;
         const int64_t tile = work % ntiles;
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         AccumItem items[kAccumItems][RG];
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
@@ -782,7 +782,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
             const int64_t a = (tile << kChunkShift) + a_rel;
             const bool live = a < tb.arena_elems;
             TensorDesc d{};
-            if (live) d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            if (live) d = tile_desc(tb, t_lo, n, a_rel, lds);
 #pragma unroll
             for (int k = 0; k < RG; ++k) {
                 const int rl = rl0 + k;
@@ -811,13 +811,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
         const int rl0 = static_cast<int>(work / ntiles) * RG;
         const int64_t tile = work % ntiles;
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
             const int64_t a = (tile << kChunkShift) + a_rel;
             if (a >= tb.arena_elems) continue;
-            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
 #pragma unroll
             for (int k = 0; k < RG; ++k) {
                 const int rl = rl0 + k;
@@ -919,13 +919,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
         const int64_t tile = work % ntiles;
         float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
             const int64_t a = (tile << kChunkShift) + a_rel;
             if (a >= tb.arena_elems) continue;
-            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
             const int64_t slot = a - d.shard_off;
             const int cnt = valid_from(d, r0 + rl, slot, 4);
             // gradient element that pairs with arena element a: goff + a
@@ -1000,13 +1000,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
         const int64_t tile = work % ntiles;
         const int r = r0 + rl;
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         if (flags[static_cast<int64_t>(r) * R + worker] != 0) continue;  // uniform per workgroup
         uint16_t *dst = static_cast<uint16_t *>(staging.p[rl]) + static_cast<int64_t>(worker) * slot;
         const int a_rel = 8 * static_cast<int>(threadIdx.x);
         const int64_t a = (tile << kChunkShift) + a_rel;
         if (a >= tb.arena_elems) continue;
-        const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+        const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
         const int64_t slot_in = a - d.shard_off;
         const int cnt = valid_from(d, r, slot_in, 8);
         const uint16_t *src = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot_in;
@@ -1132,7 +1132,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
         const int64_t tile = work % ntiles;
         const int r = r0 + rl;
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         const int32_t *list = snapshot + static_cast<int64_t>(r) * (R + 1);
         if (list[0] == 0) continue;
         float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
@@ -1142,7 +1142,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
             const int64_t a = (tile << kChunkShift) + a_rel;
             if (a >= tb.arena_elems) continue;
-            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
             const int cnt = valid_from(d, r, a - d.shard_off, 4);
             if (cnt == 4) {
                 f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);
@@ -1229,13 +1229,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
         const int rl0 = static_cast<int>(work / ntiles) * RG;
         const int64_t tile = work % ntiles;
         int t_lo, n;
-        stage_tile<false, 1>(tb, tile, ntiles, lds, t_lo, n);
+        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
             const int64_t a = (tile << kChunkShift) + a_rel;
             if (a >= tb.arena_elems) continue;
-            const TensorDesc d = tb.desc[n == 1 ? t_lo : tile_tensor(t_lo, n, a_rel, lds)];
+            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
 #pragma unroll
             for (int k = 0; k < RG; ++k) {
                 const int rl = rl0 + k;
