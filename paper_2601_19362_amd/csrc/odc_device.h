@@ -704,16 +704,23 @@ struct AccumItem {
     int cnt;  // valid elements: 4 = whole vector, 1..3 = ragged end of a shard, 0 = nothing
 };
 
+// A ragged item (1..3 valid elements at the end of a shard piece) still uses the two wide
+// loads -- the extra lanes read the next piece or alignment padding and are never stored --
+// unless that would run past the end of the arena or of the gradient buffer.  Keeping the
+// load phase uniform matters: nearly every wavefront of a many-small-tensor layout holds a
+// ragged item, and an element-wise load path would triple its memory instructions.
 template <bool NT, bool ATOMIC>
 __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc &d, int r, int64_t a,
-                                                float *__restrict__ arena, const uint16_t *__restrict__ grad)
+                                                float *__restrict__ arena, const uint16_t *__restrict__ grad,
+                                                int64_t arena_elems, int64_t full_elems)
 {
     const int64_t slot = a - d.shard_off;
     it.cnt = valid_from(d, r, slot, 4);
     it.ap = arena + a;
     if (it.cnt == 0) return;
-    const uint16_t *gp = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot;
-    if (it.cnt == 4) {
+    const int64_t goff = d.full_off + static_cast<int64_t>(r) * d.S + slot;
+    const uint16_t *gp = grad + goff;
+    if (it.cnt == 4 || (a + 4 <= arena_elems && goff + 4 <= full_elems)) {
         it.g = ld_u64_unaligned<NT>(gp);
         if constexpr (!ATOMIC) it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(it.ap));
     } else {
@@ -788,7 +795,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
                 const int rl = rl0 + k;
                 items[u][k].cnt = 0;
                 if (live && rl < nr)
-                    accum_item_load<NT, ATOMIC>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad);
+                    accum_item_load<NT, ATOMIC>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad,
+                                                tb.arena_elems, tb.full_elems);
             }
         }
 #pragma unroll
@@ -847,8 +855,11 @@ struct GradPtrs {
     const uint16_t *p[kMaxFused];
 };
 
+// One accumulator vector; `cnt` < 4 marks a ragged item whose loads are still wide (the
+// caller has checked that they stay inside the buffers) and whose first cnt results are kept.
 template <int K, bool ATOMIC>
-__device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q)
+__device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q,
+                                                int cnt = 4)
 {
     u32x2 gv[K];
 #pragma unroll
@@ -859,14 +870,20 @@ __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const G
 #pragma unroll
         for (int k = 1; k < K; ++k) sum = add4<false>(sum, gv[k], 1.0f);
         unsafeAtomicAdd(acc + 4 * q + 0, sum.x);
-        unsafeAtomicAdd(acc + 4 * q + 1, sum.y);
-        unsafeAtomicAdd(acc + 4 * q + 2, sum.z);
-        unsafeAtomicAdd(acc + 4 * q + 3, sum.w);
+        if (cnt > 1) unsafeAtomicAdd(acc + 4 * q + 1, sum.y);
+        if (cnt > 2) unsafeAtomicAdd(acc + 4 * q + 2, sum.z);
+        if (cnt > 3) unsafeAtomicAdd(acc + 4 * q + 3, sum.w);
     } else {
         f32x4 a = ld<true>(av);
 #pragma unroll
         for (int k = 0; k < K; ++k) a = add4<false>(a, gv[k], 1.0f);
-        st<true>(av, a);
+        if (cnt == 4) {
+            st<true>(av, a);
+        } else {
+            st_f32(acc + 4 * q, a.x);
+            if (cnt > 1) st_f32(acc + 4 * q + 1, a.y);
+            if (cnt > 2) st_f32(acc + 4 * q + 2, a.z);
+        }
     }
 }
 
@@ -930,7 +947,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
             const int cnt = valid_from(d, r0 + rl, slot, 4);
             // gradient element that pairs with arena element a: goff + a
             const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
-            if (cnt == 4) accum_multi_vec<K, ATOMIC>(arena, grads, goff, a >> 2);
+            if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
+                accum_multi_vec<K, ATOMIC>(arena, grads, goff, a >> 2, cnt);
             else
                 for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
         }
@@ -1010,9 +1028,19 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
         const int64_t slot_in = a - d.shard_off;
         const int cnt = valid_from(d, r, slot_in, 8);
         const uint16_t *src = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot_in;
-        if (cnt == 8) st<NT>(reinterpret_cast<u32x4 *>(dst + a), ld_u128_unaligned<NT>(src));
-        else
+        if (cnt == 8) {
+            st<NT>(reinterpret_cast<u32x4 *>(dst + a), ld_u128_unaligned<NT>(src));
+        } else if (cnt > 0 && d.full_off + static_cast<int64_t>(r) * d.S + slot_in + 8 <= tb.full_elems) {
+            // ragged end of a shard piece: one wide load (the extra lanes belong to the next
+            // piece and are dropped), element stores
+            const u32x4 v = ld_u128_unaligned<NT>(src);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 7; ++e)
+                if (e < cnt) st_u16(dst + a + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
+        } else {
             for (int e = 0; e < cnt; ++e) st_u16(dst + a + e, ld_u16(src + e));
+        }
     }
 }
 
@@ -1147,6 +1175,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
             if (cnt == 4) {
                 f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);
                 st<NT>(av, drain_vec<NT>(ld<NT>(av), stage, slot, a, list));
+            } else if (cnt > 0 && a + 4 <= tb.arena_elems) {
+                // ragged end of a shard piece: wide loads (every staging slot is at least as
+                // long as the arena rounded up to 8), element stores
+                const f32x4 sum = drain_vec<NT>(ld<NT>(reinterpret_cast<const f32x4 *>(arena + a)), stage, slot, a, list);
+                st_f32(arena + a, sum.x);
+                if (cnt > 1) st_f32(arena + a + 1, sum.y);
+                if (cnt > 2) st_f32(arena + a + 2, sum.z);
             } else {
                 for (int e = 0; e < cnt; ++e) st_f32(arena + a + e, drain_one(ld_f32(arena + a + e), stage, slot, a + e, list));
             }
@@ -1216,6 +1251,10 @@ __global__ __launch_bounds__(TPB) void k_retrieve_flat(RankPtrs accs, RankPtrs o
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) retrieve_one<BF16>(acc, out, 4 * nvec + threadIdx.x, scale);
 }
 
+// Two phases like the accumulate kernel: all loads of a thread's items first, then the stores
+// (the compiler cannot move a load above an earlier store by itself: for all it knows the
+// output shard may alias an accumulator).  A ragged item uses the wide load too where that
+// stays inside the arena; only its stores are element-wise.
 template <int RG, bool NT, bool BF16>
 __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable tb, RankPtrs accs, RankPtrs outs,
                                                                     int r0, int nr, float scale)
@@ -1230,22 +1269,63 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
         const int64_t tile = work % ntiles;
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
+        f32x4 v[kAccumItems][RG];
+        int cnt[kAccumItems][RG];
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
             const int64_t a = (tile << kChunkShift) + a_rel;
-            if (a >= tb.arena_elems) continue;
-            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
+            const bool live = a < tb.arena_elems;
+            TensorDesc d{};
+            if (live) d = tile_desc(tb, t_lo, n, a_rel, lds);
 #pragma unroll
             for (int k = 0; k < RG; ++k) {
                 const int rl = rl0 + k;
-                if (rl >= nr) continue;
-                const float *src = static_cast<const float *>(accs.p[rl]);
-                void *out = outs.p[rl];
-                const int cnt = valid_from(d, r0 + rl, a - d.shard_off, 4);
-                if (cnt == 4) retrieve_vec<NT, BF16, false>(src, out, a >> 2, scale);
-                else
-                    for (int e = 0; e < cnt; ++e) retrieve_one<BF16>(src, out, a + e, scale);
+                cnt[u][k] = 0;
+                v[u][k] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (!live || rl >= nr) continue;
+                const float *src = static_cast<const float *>(accs.p[rl]) + a;
+                const int c = valid_from(d, r0 + rl, a - d.shard_off, 4);
+                cnt[u][k] = c;
+                if (c == 4 || (c > 0 && a + 4 <= tb.arena_elems)) {
+                    v[u][k] = ld<NT>(reinterpret_cast<const f32x4 *>(src));
+                } else if (c > 0) {  // the last item of the arena
+                    v[u][k].x = ld_f32(src);
+                    if (c > 1) v[u][k].y = ld_f32(src + 1);
+                    if (c > 2) v[u][k].z = ld_f32(src + 2);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kAccumItems; ++u) {
+            const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+#pragma unroll
+            for (int k = 0; k < RG; ++k) {
+                const int c = cnt[u][k];
+                if (c == 0) continue;
+                const f32x4 s = {scale * v[u][k].x, scale * v[u][k].y, scale * v[u][k].z, scale * v[u][k].w};
+                void *out = outs.p[rl0 + k];
+                if constexpr (BF16) {
+                    uint16_t *o = static_cast<uint16_t *>(out) + a;
+                    if (c == 4) {
+                        const u32x2 p = {narrow_bf16(s.x) | (narrow_bf16(s.y) << 16),
+                                         narrow_bf16(s.z) | (narrow_bf16(s.w) << 16)};
+                        st<NT>(reinterpret_cast<u32x2 *>(o), p);
+                    } else {
+                        st_u16(o, static_cast<uint16_t>(narrow_bf16(s.x)));
+                        if (c > 1) st_u16(o + 1, static_cast<uint16_t>(narrow_bf16(s.y)));
+                        if (c > 2) st_u16(o + 2, static_cast<uint16_t>(narrow_bf16(s.z)));
+                    }
+                } else {
+                    float *o = static_cast<float *>(out) + a;
+                    if (c == 4) {
+                        st<NT>(reinterpret_cast<f32x4 *>(o), s);
+                    } else {
+                        st_f32(o, s.x);
+                        if (c > 1) st_f32(o + 1, s.y);
+                        if (c > 2) st_f32(o + 2, s.z);
+                    }
+                }
             }
         }
     }
