@@ -239,21 +239,10 @@ __device__ __forceinline__ f32x4 add4(f32x4 a, u32x2 g, float w)
     return a;
 }
 
-// Unordered contribution: device-scope float atomics (the weighted product is rounded first).
-template <bool WEIGHTED>
-__device__ __forceinline__ void atomic_add4(float *a, u32x2 g, float w)
-{
-    const float s = WEIGHTED ? w : 1.0f;
-    unsafeAtomicAdd(a + 0, WEIGHTED ? s * widen_lo(g.x) : widen_lo(g.x));
-    unsafeAtomicAdd(a + 1, WEIGHTED ? s * widen_hi(g.x) : widen_hi(g.x));
-    unsafeAtomicAdd(a + 2, WEIGHTED ? s * widen_lo(g.y) : widen_lo(g.y));
-    unsafeAtomicAdd(a + 3, WEIGHTED ? s * widen_hi(g.y) : widen_hi(g.y));
-}
-
 // A work item is one accumulator vector (4 floats, 16 bytes) and 8 bytes of gradient;
 // consecutive lanes take consecutive vectors, so every wave instruction is contiguous
 // (1 KiB of accumulator, 512 B of gradient).
-template <int TPB, int U, bool NT, bool ATOMIC, bool WEIGHTED, bool GUARD>
+template <int TPB, int U, bool NT, bool WEIGHTED, bool GUARD>
 __device__ __forceinline__ void accum_tile(float *__restrict__ acc, const uint16_t *__restrict__ g,
                                            int64_t q0, int64_t nitem, float w)
 {
@@ -265,16 +254,35 @@ __device__ __forceinline__ void accum_tile(float *__restrict__ acc, const uint16
         const int64_t q = q0 + u * TPB;
         if (!GUARD || q < nitem) {
             gv[u] = ld_u64_unaligned<NT>(g + 4 * q);
-            if constexpr (!ATOMIC) av[u] = ld<NT>(accv + q);
+            av[u] = ld<NT>(accv + q);
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int64_t q = q0 + u * TPB;
-        if (!GUARD || q < nitem) {
-            if constexpr (ATOMIC) atomic_add4<WEIGHTED>(acc + 4 * q, gv[u], w);
-            else st<NT>(accv + q, add4<WEIGHTED>(av[u], gv[u], w));
-        }
+        if (!GUARD || q < nitem) st<NT>(accv + q, add4<WEIGHTED>(av[u], gv[u], w));
+    }
+}
+
+// Unordered form of a tile (device-scope float atomics; a weighted product is rounded
+// first): consecutive lanes take consecutive ELEMENTS, so that one atomic
+// instruction of a wavefront covers 256 contiguous bytes (two cache lines) instead of four
+// floats out of every 16 bytes over 1 KiB (eight lines): the atomic units of the L2 work per
+// cache line, and the coalesced form is several times faster.
+template <int TPB, int E, bool WEIGHTED, bool GUARD>
+__device__ __forceinline__ void accum_tile_atomic(float *__restrict__ acc, const uint16_t *__restrict__ g,
+                                                  int64_t e0, int64_t n, float w)
+{
+    uint16_t gv[E];
+#pragma unroll
+    for (int u = 0; u < E; ++u) {
+        const int64_t e = e0 + u * TPB;
+        if (!GUARD || e < n) gv[u] = ld_u16(g + e);
+    }
+#pragma unroll
+    for (int u = 0; u < E; ++u) {
+        const int64_t e = e0 + u * TPB;
+        if (!GUARD || e < n) unsafeAtomicAdd(acc + e, WEIGHTED ? w * widen_one(gv[u]) : widen_one(gv[u]));
     }
 }
 
@@ -295,8 +303,13 @@ __global__ __launch_bounds__(TPB) void k_accum_flat(RankPtrs accs, const uint16_
     const int64_t nslots = slots_of(ntiles, remap);
     for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
         const int64_t t0 = tile_of(slot, ntiles, remap) * (TPB * U);
-        if (t0 + TPB * U <= nitem) accum_tile<TPB, U, NT, ATOMIC, WEIGHTED, false>(acc, g, t0 + threadIdx.x, nitem, w);
-        else if (t0 < nitem) accum_tile<TPB, U, NT, ATOMIC, WEIGHTED, true>(acc, g, t0 + threadIdx.x, nitem, w);
+        if constexpr (ATOMIC) {
+            if (t0 + TPB * U <= nitem) accum_tile_atomic<TPB, 4 * U, WEIGHTED, false>(acc, g, 4 * t0 + threadIdx.x, 4 * nitem, w);
+            else if (t0 < nitem) accum_tile_atomic<TPB, 4 * U, WEIGHTED, true>(acc, g, 4 * t0 + threadIdx.x, 4 * nitem, w);
+        } else {
+            if (t0 + TPB * U <= nitem) accum_tile<TPB, U, NT, WEIGHTED, false>(acc, g, t0 + threadIdx.x, nitem, w);
+            else if (t0 < nitem) accum_tile<TPB, U, NT, WEIGHTED, true>(acc, g, t0 + threadIdx.x, nitem, w);
+        }
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail) {
         const int64_t k = 4 * nitem + threadIdx.x;
@@ -709,7 +722,7 @@ struct AccumItem {
 // unless that would run past the end of the arena or of the gradient buffer.  Keeping the
 // load phase uniform matters: nearly every wavefront of a many-small-tensor layout holds a
 // ragged item, and an element-wise load path would triple its memory instructions.
-template <bool NT, bool ATOMIC>
+template <bool NT>
 __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc &d, int r, int64_t a,
                                                 float *__restrict__ arena, const uint16_t *__restrict__ grad,
                                                 int64_t arena_elems, int64_t full_elems)
@@ -722,44 +735,31 @@ __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc 
     const uint16_t *gp = grad + goff;
     if (it.cnt == 4 || (a + 4 <= arena_elems && goff + 4 <= full_elems)) {
         it.g = ld_u64_unaligned<NT>(gp);
-        if constexpr (!ATOMIC) it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(it.ap));
+        it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(it.ap));
     } else {
         const uint32_t e0 = ld_u16(gp);
         const uint32_t e1 = it.cnt > 1 ? ld_u16(gp + 1) : 0u;
         const uint32_t e2 = it.cnt > 2 ? ld_u16(gp + 2) : 0u;
         it.g.x = e0 | (e1 << 16);
         it.g.y = e2;
-        if constexpr (!ATOMIC) {
-            it.acc.x = ld_f32(it.ap);
-            it.acc.y = it.cnt > 1 ? ld_f32(it.ap + 1) : 0.0f;
-            it.acc.z = it.cnt > 2 ? ld_f32(it.ap + 2) : 0.0f;
-            it.acc.w = 0.0f;
-        }
+        it.acc.x = ld_f32(it.ap);
+        it.acc.y = it.cnt > 1 ? ld_f32(it.ap + 1) : 0.0f;
+        it.acc.z = it.cnt > 2 ? ld_f32(it.ap + 2) : 0.0f;
+        it.acc.w = 0.0f;
     }
 }
 
-template <bool NT, bool ATOMIC, bool WEIGHTED>
+template <bool NT, bool WEIGHTED>
 __device__ __forceinline__ void accum_item_store(const AccumItem &it, float w)
 {
     if (it.cnt == 0) return;
-    if constexpr (ATOMIC) {
-        if (it.cnt == 4) {
-            atomic_add4<WEIGHTED>(it.ap, it.g, w);
-        } else {
-            const float s = WEIGHTED ? w : 1.0f;
-            unsafeAtomicAdd(it.ap, WEIGHTED ? s * widen_lo(it.g.x) : widen_lo(it.g.x));
-            if (it.cnt > 1) unsafeAtomicAdd(it.ap + 1, WEIGHTED ? s * widen_hi(it.g.x) : widen_hi(it.g.x));
-            if (it.cnt > 2) unsafeAtomicAdd(it.ap + 2, WEIGHTED ? s * widen_lo(it.g.y) : widen_lo(it.g.y));
-        }
+    const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);  // lanes beyond cnt are computed but never stored
+    if (it.cnt == 4) {
+        st<NT>(reinterpret_cast<f32x4 *>(it.ap), sum);
     } else {
-        const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);  // lanes beyond cnt are computed but never stored
-        if (it.cnt == 4) {
-            st<NT>(reinterpret_cast<f32x4 *>(it.ap), sum);
-        } else {
-            st_f32(it.ap, sum.x);
-            if (it.cnt > 1) st_f32(it.ap + 1, sum.y);
-            if (it.cnt > 2) st_f32(it.ap + 2, sum.z);
-        }
+        st_f32(it.ap, sum.x);
+        if (it.cnt > 1) st_f32(it.ap + 1, sum.y);
+        if (it.cnt > 2) st_f32(it.ap + 2, sum.z);
     }
 }
 
@@ -782,27 +782,59 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
         const int64_t tile = work % ntiles;
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
-        AccumItem items[kAccumItems][RG];
+        if constexpr (ATOMIC) {
+            // unordered: one element per lane and step, so that every atomic instruction of a
+            // wavefront covers contiguous bytes (see accum_tile_atomic)
+            constexpr int E = kChunkElems / kBatchThreads;
+            uint16_t gv[E][RG];
+            bool on[E][RG];
 #pragma unroll
-        for (int u = 0; u < kAccumItems; ++u) {
-            const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
-            const int64_t a = (tile << kChunkShift) + a_rel;
-            const bool live = a < tb.arena_elems;
-            TensorDesc d{};
-            if (live) d = tile_desc(tb, t_lo, n, a_rel, lds);
+            for (int u = 0; u < E; ++u) {
+                const int a_rel = u * kBatchThreads + static_cast<int>(threadIdx.x);
+                const int64_t a = (tile << kChunkShift) + a_rel;
+                const bool live = a < tb.arena_elems;
+                TensorDesc d{};
+                if (live) d = tile_desc(tb, t_lo, n, a_rel, lds);
 #pragma unroll
-            for (int k = 0; k < RG; ++k) {
-                const int rl = rl0 + k;
-                items[u][k].cnt = 0;
-                if (live && rl < nr)
-                    accum_item_load<NT, ATOMIC>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad,
-                                                tb.arena_elems, tb.full_elems);
+                for (int k = 0; k < RG; ++k) {
+                    const int rl = rl0 + k;
+                    on[u][k] = live && rl < nr && valid_from(d, r0 + rl, a - d.shard_off, 1) == 1;
+                    gv[u][k] = 0;
+                    if (on[u][k]) gv[u][k] = ld_u16(grad + d.full_off + static_cast<int64_t>(r0 + rl) * d.S + (a - d.shard_off));
+                }
             }
+#pragma unroll
+            for (int u = 0; u < E; ++u) {
+                const int64_t a = (tile << kChunkShift) + u * kBatchThreads + static_cast<int>(threadIdx.x);
+#pragma unroll
+                for (int k = 0; k < RG; ++k)
+                    if (on[u][k])
+                        unsafeAtomicAdd(static_cast<float *>(accs.p[rl0 + k]) + a,
+                                        WEIGHTED ? w * widen_one(gv[u][k]) : widen_one(gv[u][k]));
+            }
+        } else {
+            AccumItem items[kAccumItems][RG];
+#pragma unroll
+            for (int u = 0; u < kAccumItems; ++u) {
+                const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+                const int64_t a = (tile << kChunkShift) + a_rel;
+                const bool live = a < tb.arena_elems;
+                TensorDesc d{};
+                if (live) d = tile_desc(tb, t_lo, n, a_rel, lds);
+#pragma unroll
+                for (int k = 0; k < RG; ++k) {
+                    const int rl = rl0 + k;
+                    items[u][k].cnt = 0;
+                    if (live && rl < nr)
+                        accum_item_load<NT>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad,
+                                            tb.arena_elems, tb.full_elems);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kAccumItems; ++u)
+#pragma unroll
+                for (int k = 0; k < RG; ++k) accum_item_store<NT, WEIGHTED>(items[u][k], w);
         }
-#pragma unroll
-        for (int u = 0; u < kAccumItems; ++u)
-#pragma unroll
-            for (int k = 0; k < RG; ++k) accum_item_store<NT, ATOMIC, WEIGHTED>(items[u][k], w);
     }
 }
 
@@ -855,9 +887,10 @@ struct GradPtrs {
     const uint16_t *p[kMaxFused];
 };
 
-// One accumulator vector; `cnt` < 4 marks a ragged item whose loads are still wide (the
-// caller has checked that they stay inside the buffers) and whose first cnt results are kept.
-template <int K, bool ATOMIC>
+// One accumulator vector (ordered form); `cnt` < 4 marks a ragged item whose loads are still
+// wide (the caller has checked that they stay inside the buffers) and whose first cnt results
+// are kept.
+template <int K>
 __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q,
                                                 int cnt = 4)
 {
@@ -865,36 +898,36 @@ __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const G
 #pragma unroll
     for (int k = 0; k < K; ++k) gv[k] = ld_u64_unaligned<true>(grads.p[k] + goff + 4 * q);
     f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
-    if constexpr (ATOMIC) {
-        f32x4 sum = {widen_lo(gv[0].x), widen_hi(gv[0].x), widen_lo(gv[0].y), widen_hi(gv[0].y)};
+    f32x4 a = ld<true>(av);
 #pragma unroll
-        for (int k = 1; k < K; ++k) sum = add4<false>(sum, gv[k], 1.0f);
-        unsafeAtomicAdd(acc + 4 * q + 0, sum.x);
-        if (cnt > 1) unsafeAtomicAdd(acc + 4 * q + 1, sum.y);
-        if (cnt > 2) unsafeAtomicAdd(acc + 4 * q + 2, sum.z);
-        if (cnt > 3) unsafeAtomicAdd(acc + 4 * q + 3, sum.w);
+    for (int k = 0; k < K; ++k) a = add4<false>(a, gv[k], 1.0f);
+    if (cnt == 4) {
+        st<true>(av, a);
     } else {
-        f32x4 a = ld<true>(av);
-#pragma unroll
-        for (int k = 0; k < K; ++k) a = add4<false>(a, gv[k], 1.0f);
-        if (cnt == 4) {
-            st<true>(av, a);
-        } else {
-            st_f32(acc + 4 * q, a.x);
-            if (cnt > 1) st_f32(acc + 4 * q + 1, a.y);
-            if (cnt > 2) st_f32(acc + 4 * q + 2, a.z);
-        }
+        st_f32(acc + 4 * q, a.x);
+        if (cnt > 1) st_f32(acc + 4 * q + 1, a.y);
+        if (cnt > 2) st_f32(acc + 4 * q + 2, a.z);
     }
+}
+
+// Sum of the K values of one element, left to right (unordered form: added atomically).
+template <int K>
+__device__ __forceinline__ float multi_sum_one(const GradPtrs &grads, int64_t goff, int64_t e)
+{
+    uint16_t gv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) gv[k] = ld_u16(grads.p[k] + goff + e);
+    float sum = widen_one(gv[0]);
+#pragma unroll
+    for (int k = 1; k < K; ++k) sum = sum + widen_one(gv[k]);
+    return sum;
 }
 
 template <int K, bool ATOMIC>
 __device__ __forceinline__ void accum_multi_one(float *acc, const GradPtrs &grads, int64_t goff, int64_t e)
 {
     if constexpr (ATOMIC) {
-        float sum = widen_one(ld_u16(grads.p[0] + goff + e));
-#pragma unroll
-        for (int k = 1; k < K; ++k) sum = sum + widen_one(ld_u16(grads.p[k] + goff + e));
-        unsafeAtomicAdd(acc + e, sum);
+        unsafeAtomicAdd(acc + e, multi_sum_one<K>(grads, goff, e));
     } else {
         float a = ld_f32(acc + e);
 #pragma unroll
@@ -915,8 +948,24 @@ __global__ __launch_bounds__(64) void k_accum_multi_flat(RankPtrs accs, GradPtrs
     const int tail = static_cast<int>(valid & 3);
     const int64_t ntiles = (nitem + 63) >> 6;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t q = (tile << 6) + threadIdx.x;
-        if (q < nitem) accum_multi_vec<K, ATOMIC>(acc, grads, base, q);
+        if constexpr (ATOMIC) {
+            // one element per lane and step: contiguous atomics (see accum_tile_atomic)
+            float sum[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t e = (tile << 8) + u * 64 + threadIdx.x;
+                sum[u] = 0.0f;
+                if (e < 4 * nitem) sum[u] = multi_sum_one<K>(grads, base, e);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t e = (tile << 8) + u * 64 + threadIdx.x;
+                if (e < 4 * nitem) unsafeAtomicAdd(acc + e, sum[u]);
+            }
+        } else {
+            const int64_t q = (tile << 6) + threadIdx.x;
+            if (q < nitem) accum_multi_vec<K>(acc, grads, base, q);
+        }
     }
     if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < tail)
         accum_multi_one<K, ATOMIC>(acc, grads, base, 4 * nitem + threadIdx.x);
@@ -937,6 +986,27 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
         float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
+        if constexpr (ATOMIC) {
+            constexpr int E = kChunkElems / kBatchThreads;
+            float sum[E];
+            bool on[E];
+#pragma unroll
+            for (int u = 0; u < E; ++u) {
+                const int a_rel = u * kBatchThreads + static_cast<int>(threadIdx.x);
+                const int64_t a = (tile << kChunkShift) + a_rel;
+                on[u] = false;
+                sum[u] = 0.0f;
+                if (a >= tb.arena_elems) continue;
+                const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
+                const int64_t slot = a - d.shard_off;
+                on[u] = valid_from(d, r0 + rl, slot, 1) == 1;
+                if (on[u]) sum[u] = multi_sum_one<K>(grads, d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a, a);
+            }
+#pragma unroll
+            for (int u = 0; u < E; ++u)
+                if (on[u]) unsafeAtomicAdd(arena + (tile << kChunkShift) + u * kBatchThreads + static_cast<int>(threadIdx.x), sum[u]);
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
@@ -948,7 +1018,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
             // gradient element that pairs with arena element a: goff + a
             const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
             if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
-                accum_multi_vec<K, ATOMIC>(arena, grads, goff, a >> 2, cnt);
+                accum_multi_vec<K>(arena, grads, goff, a >> 2, cnt);
             else
                 for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
         }
