@@ -49,6 +49,15 @@ struct RankPtrs {
 #define ODC_GLOBAL
 #endif
 
+// Register budget of a kernel, as the number of wavefronts per SIMD it must allow (512 vector
+// registers per SIMD: 8 wavefronts = 64 registers each).  Used where the compiler lands one
+// register above a boundary.  (Empty in the CPU emulation build.)
+#ifdef __HIP__
+#define ODC_WAVES_PER_EU(n) __attribute__((amdgpu_waves_per_eu(n)))
+#else
+#define ODC_WAVES_PER_EU(n)
+#endif
+
 template <bool NT, typename V>
 __device__ __forceinline__ V ld(const V *p)
 {
@@ -713,7 +722,6 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
 struct AccumItem {
     u32x2 g;
     f32x4 acc;
-    float *ap;
     int cnt;  // valid elements: 4 = whole vector, 1..3 = ragged end of a shard, 0 = nothing
 };
 
@@ -729,37 +737,37 @@ __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc 
 {
     const int64_t slot = a - d.shard_off;
     it.cnt = valid_from(d, r, slot, 4);
-    it.ap = arena + a;
+    const float *ap = arena + a;
     if (it.cnt == 0) return;
     const int64_t goff = d.full_off + static_cast<int64_t>(r) * d.S + slot;
     const uint16_t *gp = grad + goff;
     if (it.cnt == 4 || (a + 4 <= arena_elems && goff + 4 <= full_elems)) {
         it.g = ld_u64_unaligned<NT>(gp);
-        it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(it.ap));
+        it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(ap));
     } else {
         const uint32_t e0 = ld_u16(gp);
         const uint32_t e1 = it.cnt > 1 ? ld_u16(gp + 1) : 0u;
         const uint32_t e2 = it.cnt > 2 ? ld_u16(gp + 2) : 0u;
         it.g.x = e0 | (e1 << 16);
         it.g.y = e2;
-        it.acc.x = ld_f32(it.ap);
-        it.acc.y = it.cnt > 1 ? ld_f32(it.ap + 1) : 0.0f;
-        it.acc.z = it.cnt > 2 ? ld_f32(it.ap + 2) : 0.0f;
+        it.acc.x = ld_f32(ap);
+        it.acc.y = it.cnt > 1 ? ld_f32(ap + 1) : 0.0f;
+        it.acc.z = it.cnt > 2 ? ld_f32(ap + 2) : 0.0f;
         it.acc.w = 0.0f;
     }
 }
 
 template <bool NT, bool WEIGHTED>
-__device__ __forceinline__ void accum_item_store(const AccumItem &it, float w)
+__device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap, float w)
 {
     if (it.cnt == 0) return;
     const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);  // lanes beyond cnt are computed but never stored
     if (it.cnt == 4) {
-        st<NT>(reinterpret_cast<f32x4 *>(it.ap), sum);
+        st<NT>(reinterpret_cast<f32x4 *>(ap), sum);
     } else {
-        st_f32(it.ap, sum.x);
-        if (it.cnt > 1) st_f32(it.ap + 1, sum.y);
-        if (it.cnt > 2) st_f32(it.ap + 2, sum.z);
+        st_f32(ap, sum.x);
+        if (it.cnt > 1) st_f32(ap + 1, sum.y);
+        if (it.cnt > 2) st_f32(ap + 2, sum.z);
     }
 }
 
@@ -768,7 +776,7 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float w)
 // on a few advancing address windows at a time (measurably faster than spreading every tile
 // over all owners first).
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
-__global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, RankPtrs accs,
+__global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 4) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
                                                                  float w)
 {
@@ -831,9 +839,13 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_batched(BatchTable tb, 
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kAccumItems; ++u)
+            for (int u = 0; u < kAccumItems; ++u) {
+                const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
 #pragma unroll
-                for (int k = 0; k < RG; ++k) accum_item_store<NT, WEIGHTED>(items[u][k], w);
+                for (int k = 0; k < RG; ++k)
+                    if (rl0 + k < nr)
+                        accum_item_store<NT, WEIGHTED>(items[u][k], static_cast<float *>(accs.p[rl0 + k]) + a, w);
+            }
         }
     }
 }
