@@ -1029,7 +1029,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
             const int cnt = valid_from(d, r0 + rl, slot, 4);
             // gradient element that pairs with arena element a: goff + a
             const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
-            if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
+            // a ragged item keeps the wide loads only for K <= 2 (measured: beyond that the
+            // element-wise form is faster)
+            if (cnt == 4 || (K <= 2 && cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
                 accum_multi_vec<K>(arena, grads, goff, a >> 2, cnt);
             else
                 for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
