@@ -539,3 +539,38 @@ def test_hip_graph_replay_matches_oracle(oracle, numel, R):
                 assert_bits_equal(got[a:a + v], want_out[r][a:a + v], f"replay {replay} retrieve rank {r} tensor {t}")
     case.check_guards()
     case.close()
+
+
+@pytest.mark.parametrize("numel,R", [([3_000_001], 16), ([4099, 1, 70_001, 12_345, 8, 300_000], 8)])
+def test_unordered_concurrent_streams_lose_no_update(oracle, numel, R):
+    """Small-integer gradients (exact in bf16, every partial sum exact in binary32) make the
+    result independent of the order, so the unordered mode must reproduce the ordered oracle bit
+    for bit even when 12 contributions race on three streams: a lost or doubled atomic update
+    would show as a wrong integer."""
+    print(f"unordered concurrency case R={R} numel={numel}", flush=True)
+    case = DeviceCase(R, numel, with_params=False)
+    rng = np.random.default_rng(5)
+    C = 12
+    ints = [rng.integers(-256, 257, size=case.full_n).astype(np.float32) for _ in range(C)]
+    grads = [inputs.f32_to_bf16_bits(x) for x in ints]
+    for g, x in zip(grads, ints):
+        assert np.array_equal(inputs.bf16_bits_to_f32(g), x)     # exactly representable
+    dev = [to_dev_u16(g) for g in grads]
+    case.layout.reset_accum(case.acc_ptrs)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for k in range(C):
+        if k % 4 == 3:   # every fourth through the weighted entry point with weight 1
+            case.layout.scatter_accumulate_weighted(dev[k], case.acc_ptrs, 0, 0, 1.0, odc.ODC_UNORDERED,
+                                                    stream=streams[k % 3])
+        else:
+            case.layout.scatter_accumulate(dev[k], case.acc_ptrs, 0, 0, odc.ODC_UNORDERED, stream=streams[k % 3])
+    torch.cuda.synchronize()
+    acc_host = [np.full(case.arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc_host, numel, case.shard_off)
+    for g in grads:
+        oracle.accumulate_batched(g, acc_host, numel, case.shard_off, case.full_off)
+    for r, a in enumerate(case.acc_host()):
+        assert_bits_equal(a, acc_host[r], f"unordered concurrent rank {r}")
+    case.check_guards()
+    case.close()
