@@ -776,7 +776,7 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap,
 // on a few advancing address windows at a time (measurably faster than spreading every tile
 // over all owners first).
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
-__global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 4) void k_accum_batched(BatchTable tb, RankPtrs accs,
+__global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 1) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
                                                                  float w)
 {
