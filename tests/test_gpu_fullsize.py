@@ -232,3 +232,55 @@ def test_multi_tensor_layout_with_a_2p30_element_tensor(oracle):
     for r in range(R):
         assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"accumulate rank {r}")
     L.close()
+
+
+def test_7b_layer_staging_and_fused(oracle):
+    """Server-side staging and the fused contribution at the 7B layer shape (7.5 GB of staging
+    slots): three clients push, the owners drain in client order; two more push and are drained;
+    then three contributions go through the fused entry point.  All compared with the oracle's
+    single ordered contributions in the same order."""
+    w = inputs.workload("7b")
+    N, R = w.numel[0], w.R
+    print(f"7b staging case N={N} R={R}", flush=True)
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    slot = L.stage_slot_elems()
+    bufs = [torch.empty(R * slot, dtype=torch.bfloat16, device=dev) for _ in range(R)]
+    flags = torch.full((L.stage_flag_count(),), 5, dtype=torch.int32, device=dev)
+    snap = torch.zeros(L.stage_snapshot_count(), dtype=torch.int32, device=dev)
+    L.stage_init(flags)
+    acc = [torch.full((S,), 3.25, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc_h = [np.full(S, 3.25, dtype=np.float32) for _ in range(R)]
+    L.reset_accum(acc)
+    oracle.reset(acc_h, N, nthreads=THREADS)
+
+    def host(g):
+        return g.view(torch.int16).cpu().numpy().view(np.uint16)
+
+    seed = [700]
+
+    def fresh():
+        seed[0] += 1
+        return inputs.device_normal_bf16(N, 1e-3, seed[0], dev)
+
+    for clients in ([3, 0, 9], [15, 0]):
+        staged = {}
+        for c in clients:
+            g = fresh()
+            L.stage_push(g, bufs, flags, c)
+            staged[c] = host(g)
+            del g
+        L.stage_drain(bufs, flags, snap, acc)
+        for c in sorted(staged):                      # the drain adds in ascending client order
+            oracle.accumulate(staged[c], acc_h, N, nthreads=THREADS)
+    torch.cuda.synchronize()
+    assert not flags.cpu().numpy().any()
+    grads = [fresh() for _ in range(3)]
+    L.scatter_accumulate_multi(grads, acc, [1, 1, 2], [0, 1, 0])
+    for g in grads:
+        oracle.accumulate(host(g), acc_h, N, nthreads=THREADS)
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"staged + fused accumulate rank {r}")
+    L.close()
