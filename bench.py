@@ -210,10 +210,17 @@ def cpu_baseline(w, target_s):
         n_acc += 1
         nbytes += total * 10
     dt = time.perf_counter() - t0
-    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": (f"one parameter set of workload {w.name}: 1 reset + 2 gathers + {n_acc} "
-                       f"contributions (same gradient buffer reused), {dt:.1f} s of host time, "
-                       "same 4/10 B-per-element rule")}
+    out = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "sample": (f"one parameter set of workload {w.name}: 1 reset + 2 gathers + {n_acc} "
+                      f"contributions (same gradient buffer reused), {dt:.1f} s of host time, "
+                      "same 4/10 B-per-element rule")}
+    if len(numel) == 1 and cores > 1:
+        # the same oracle on one thread: one gather and one contribution
+        t1 = time.perf_counter()
+        oracle.gather(shards, N, full, nthreads=1)
+        oracle.accumulate(g, acc, N, nthreads=1)
+        out["single_thread_value"] = round(total * 14 / (time.perf_counter() - t1) / 1e9, 3)
+    return out
 
 
 def main():
