@@ -23,7 +23,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(CLANG), reason="ROCm clang++ 
 
 
 def start_build(exe, *defines):
-    return subprocess.Popen([CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+    return subprocess.Popen([CLANG, "-std=c++17", "-O0", "-g", "-fsanitize=address,undefined",
                              "-fno-sanitize-recover=all", "-ffp-contract=off", "-pthread", *defines,
                              os.path.join(ROOT, "tests", "cpu_emu", "emu_main.cpp"),
                              os.path.join(ROOT, "paper_2601_19362_amd", "csrc", "odc_layout.cpp"),
