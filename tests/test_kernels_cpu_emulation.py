@@ -257,3 +257,67 @@ def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
     flags = np.fromfile(tmp_path / "flags.out", dtype=np.int32)
     assert flags[:R * R].reshape(R, R).astype(bool).tolist() == model.full
     assert flags[R * R] == model.refused and model.refused >= R     # at least the second push of worker 0
+
+
+def random_layout(seed):
+    """A seeded random multi-tensor layout: tensor sizes from a mixture of tiny, small, medium
+    and large, a rank count from single-launch and multi-launch values; at most about 250,000
+    elements in all so that a case runs in a second."""
+    rng = np.random.default_rng(seed)
+    R = int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64, 65, 130]))
+    T = int(rng.integers(2, 40))
+    sizes = []
+    for _ in range(T):
+        kind = rng.choice(4, p=[0.35, 0.3, 0.25, 0.1])
+        hi = [16, 600, 20_000, 70_000][kind]
+        lo = [1, 17, 601, 20_001][kind]
+        sizes.append(int(rng.integers(lo, hi + 1)))
+    while sum(sizes) > 250_000:
+        sizes.remove(max(sizes))
+    if len(sizes) < 2:
+        sizes.append(5)
+    return sizes, R
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_emulated_random_layouts(oracle, emu, emu_low_limit, tmp_path, seed):
+    """Gather (both builds), reset, one ordered and one unordered contribution and a retrieval on
+    a random layout; every buffer compared in full with the oracle."""
+    numel, R = random_layout(1000 + seed)
+    rg = [1, 2, 4, 8][seed % 4]
+    S, so, fo, arena, full_n, arenas, flats = make_case(oracle, numel, R, seed=40 + seed)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    np.concatenate(arenas).tofile(tmp_path / "arenas.u16")
+    want = np.full(full_n, 0xBEEF, dtype=np.uint16)
+    oracle.gather_batched(arenas, numel, so, fo, want)
+    for exe in (emu, emu_low_limit):
+        np.full(full_n, 0xBEEF, dtype=np.uint16).tofile(tmp_path / "full.u16")
+        run(exe, tmp_path, "gather", R, nt=seed % 2)
+        assert np.array_equal(np.fromfile(tmp_path / "full.out", dtype=np.uint16), want), (numel, R)
+
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    run(emu, tmp_path, "reset", R, rg=rg)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    oracle.reset_batched(acc, numel, so)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32)), (numel, R)
+    for atomic in (0, 1):   # a single contribution onto zeros or onto one value: exact either way
+        g = inputs.normal_bf16(full_n, 1e-2, seed=(41, seed, atomic))
+        g.tofile(tmp_path / "grad.u16")
+        got.tofile(tmp_path / "acc.f32")
+        run(emu, tmp_path, "accum", R, atomic=atomic, rg=rg)
+        got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+        oracle.accumulate_batched(g, acc, numel, so, fo)
+        assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32)), (numel, R, atomic)
+
+    bf16 = seed % 2
+    dtype, fill = (np.uint16, 0xDEAD) if bf16 else (np.float32, PAD32)
+    out = [np.full(arena, fill, dtype=dtype) for _ in range(R)]
+    np.concatenate(out).tofile(tmp_path / "out.bin")
+    got.tofile(tmp_path / "acc.f32")
+    scale = float(np.float32(1.0 / 3.0))
+    run(emu, tmp_path, "retrieve", R, rg=rg, bf16=bf16, scale=repr(scale))
+    got_out = np.fromfile(tmp_path / "out.out", dtype=dtype)
+    oracle.retrieve_batched(acc, out, numel, so, scale=scale)
+    assert np.array_equal(got_out.view(np.uint16 if bf16 else np.uint32),
+                          np.concatenate(out).view(np.uint16 if bf16 else np.uint32)), (numel, R)
