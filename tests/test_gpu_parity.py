@@ -574,3 +574,29 @@ def test_unordered_concurrent_streams_lose_no_update(oracle, numel, R):
         assert_bits_equal(a, acc_host[r], f"unordered concurrent rank {r}")
     case.check_guards()
     case.close()
+
+
+def random_layout(seed):
+    """Seeded random multi-tensor layout, up to about 6 M elements, with single- and
+    multi-launch rank counts."""
+    rng = np.random.default_rng(seed)
+    R = int(rng.choice([1, 2, 3, 7, 8, 16, 33, 64, 65, 100, 130]))
+    T = int(rng.integers(2, 120))
+    sizes = []
+    for _ in range(T):
+        kind = rng.choice(5, p=[0.3, 0.3, 0.2, 0.15, 0.05])
+        lo, hi = [(1, 16), (17, 600), (601, 20_000), (20_001, 200_000), (200_001, 2_000_000)][kind]
+        sizes.append(int(rng.integers(lo, hi + 1)))
+    while sum(sizes) > 6_000_000:
+        sizes.remove(max(sizes))
+    if len(sizes) < 2:
+        sizes.append(5)
+    return sizes, R
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_layouts(oracle, seed):
+    numel, R = random_layout(500 + seed)
+    print(f"random layout seed={seed} R={R} T={len(numel)} total={sum(numel)}", flush=True)
+    run_case(oracle, numel, R, [(0, 0), (0, 1), (R - 1, 0)], seed=300 + seed, grad_sigma=1e-2, prange=(-1, 1))
+    weighted_retrieve_case(oracle, numel, R, seed=400 + seed, weights=[0.37, 1.0 / 3.0], scale=1.0 / 7.0)
