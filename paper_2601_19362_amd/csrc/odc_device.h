@@ -771,10 +771,10 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap,
     }
 }
 
-// One-dimensional grid over (group of RG owners, tile of the rank arena), tile fastest:
-// consecutive workgroups sweep one owner group's arenas from start to end, so the chip works
-// on a few advancing address windows at a time (measurably faster than spreading every tile
-// over all owners first).
+// Grid: x = tiles of the rank arena, y = groups of RG owners.  Workgroups are handed out x
+// first, so consecutive workgroups sweep one owner group's arenas from start to end and the
+// chip works on a few advancing address windows at a time (measurably faster than spreading
+// every tile over all owners first); and no kernel has to divide a linear work index.
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
 __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 1) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
@@ -782,12 +782,9 @@ __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 1) vo
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int ngroups = (nr + RG - 1) / RG;
-    const int64_t nwork = ntiles * ngroups;
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl0 = static_cast<int>(work / ntiles) * RG;
-        const int64_t tile = work % ntiles;
+    const int rl0 = static_cast<int>(blockIdx.y) * RG;  // grid.y = owner groups
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         if constexpr (ATOMIC) {
@@ -855,13 +852,10 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int ngroups = (nr + RG - 1) / RG;
-    const int64_t nwork = ntiles * ngroups;
+    const int rl0 = static_cast<int>(blockIdx.y) * RG;  // grid.y = owner groups
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl0 = static_cast<int>(work / ntiles) * RG;
-        const int64_t tile = work % ntiles;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
 #pragma unroll
@@ -983,18 +977,16 @@ __global__ __launch_bounds__(64) void k_accum_multi_flat(RankPtrs accs, GradPtrs
         accum_multi_one<K, ATOMIC>(acc, grads, base, 4 * nitem + threadIdx.x);
 }
 
-// Batched form: one workgroup per (owner, tile of the rank arena), tile fastest.
+// Batched form: grid x = tiles of the rank arena, y = owners.
 template <int K, bool ATOMIC>
 __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTable tb, RankPtrs accs, GradPtrs grads,
                                                                        int r0, int nr)
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int64_t nwork = ntiles * nr;
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl = static_cast<int>(work / ntiles);
-        const int64_t tile = work % ntiles;
+    const int rl = static_cast<int>(blockIdx.y);  // grid.y = owners of this launch
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         float *__restrict__ arena = static_cast<float *>(accs.p[rl]);
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1095,11 +1087,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int64_t nwork = ntiles * nr;
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl = static_cast<int>(work / ntiles);
-        const int64_t tile = work % ntiles;
+    const int rl = static_cast<int>(blockIdx.y);  // grid.y = owners of this launch
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         const int r = r0 + rl;
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1237,11 +1227,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int64_t nwork = ntiles * nr;
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl = static_cast<int>(work / ntiles);
-        const int64_t tile = work % ntiles;
+    const int rl = static_cast<int>(blockIdx.y);  // grid.y = owners of this launch
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         const int r = r0 + rl;
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
@@ -1345,12 +1333,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int ngroups = (nr + RG - 1) / RG;
-    const int64_t nwork = ntiles * ngroups;
-    for (int64_t work = blockIdx.x; work < nwork; work += gridDim.x) {
-        if (work != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int rl0 = static_cast<int>(work / ntiles) * RG;
-        const int64_t tile = work % ntiles;
+    const int rl0 = static_cast<int>(blockIdx.y) * RG;  // grid.y = owner groups
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         f32x4 v[kAccumItems][RG];

@@ -111,10 +111,11 @@ int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, v
     return finish();
 }
 
-// The batched kernels use fixed 256-thread workgroups.
-static unsigned batched_grid_x(int64_t work)
+// The batched kernels use fixed 256-thread workgroups: grid x = tiles (capped by the
+// max_grid_x knob, the kernels loop), y = owner groups for the arena-major kernels.
+static unsigned batched_grid_x(int64_t tiles)
 {
-    return grid_x_for(work, 1, tuning().max_grid_x);
+    return grid_x_for(tiles, 1, tuning().max_grid_x);
 }
 
 // Owners per workgroup in the batched accumulate / reset / retrieve kernels.  A workgroup that
@@ -166,11 +167,11 @@ int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
     const int rg = rank_group(tiles, nr, 2);
-    const int64_t work = tiles * ((nr + rg - 1) / rg);
-#define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                                   \
-    ODC_DISPATCH_RG(rg, NTF,                                                                                         \
-                    (k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>( \
-                        tb, rp, g, r0, nr, w)))
+    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
+#define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                     \
+    ODC_DISPATCH_RG(rg, NTF,                                                                           \
+                    (k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_><<<grid, kBatchThreads, 0, s>>>(tb, rp, g, r0, nr, \
+                                                                                                  w)))
     if (atomic && weighted) ODC_ACCUM_BATCHED(true, true, false);
     else if (atomic) ODC_ACCUM_BATCHED(true, false, false);
     else if (weighted) ODC_ACCUM_BATCHED(false, true, tuning().nontemporal != 0);
@@ -185,9 +186,9 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
     const int rg = rank_group(tiles, nr, 1);
-    const int64_t work = tiles * ((nr + rg - 1) / rg);
+    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
     ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
-                    (k_reset_batched<RG_, NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
+                    (k_reset_batched<RG_, NT_><<<grid, kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
     return finish();
 }
 
@@ -229,8 +230,7 @@ int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, 
     const RankPtrs rp = pack(ptrs, nr);
     const GradPtrs gp = pack_grads(grads, count);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
-    const dim3 grid(batched_grid_x(work));
+    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     if (atomic)
         ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, true><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0, nr)));
     else
@@ -262,9 +262,9 @@ int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0
 {
     const RankPtrs rp = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                    (k_stage_push_batched<NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                    (k_stage_push_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,
                         nr, worker)));
     return finish();
@@ -309,9 +309,9 @@ int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const vo
     const RankPtrs ra = pack(accs, nr);
     const RankPtrs rs = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
+    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                    (k_stage_drain_batched<NT_><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
+                    (k_stage_drain_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, ra, rs, static_cast<const int32_t *>(snapshot), slot, R, r0, nr)));
     return finish();
 }
@@ -343,15 +343,13 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
     const int rg = rank_group(tiles, nr, 2);
-    const int64_t work = tiles * ((nr + rg - 1) / rg);
+    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
     if (bf16) {
         ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
-                        (k_retrieve_batched<RG_, NT_, true><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
-                            tb, ra, ro, r0, nr, scale)));
+                        (k_retrieve_batched<RG_, NT_, true><<<grid, kBatchThreads, 0, s>>>(tb, ra, ro, r0, nr, scale)));
     } else {
         ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
-                        (k_retrieve_batched<RG_, NT_, false><<<dim3(batched_grid_x(work)), kBatchThreads, 0, s>>>(
-                            tb, ra, ro, r0, nr, scale)));
+                        (k_retrieve_batched<RG_, NT_, false><<<grid, kBatchThreads, 0, s>>>(tb, ra, ro, r0, nr, scale)));
     }
     return finish();
 }

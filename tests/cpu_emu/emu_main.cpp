@@ -65,10 +65,10 @@ void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
 // Workgroups one after the other, each on `tpb` host threads that meet at the barrier
 // behind __syncthreads().  `kernel` is called once per (thread, workgroup).
 template <typename F>
-void run_grid_threaded(unsigned tpb, unsigned gx, F &&kernel)
+void run_grid_threaded(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
 {
     gridDim.x = gx;
-    gridDim.y = 1;
+    gridDim.y = gy;
     blockDim.x = tpb;
     pthread_barrier_t barrier;
     pthread_barrier_init(&barrier, nullptr, tpb);
@@ -76,13 +76,14 @@ void run_grid_threaded(unsigned tpb, unsigned gx, F &&kernel)
     std::vector<std::thread> pool;
     for (unsigned t = 0; t < tpb; ++t)
         pool.emplace_back([&, t] {
-            for (unsigned x = 0; x < gx; ++x) {
-                blockIdx.x = x;
-                blockIdx.y = 0;
-                threadIdx.x = t;
-                kernel();
-                pthread_barrier_wait(&barrier);  // the shared LDS image is reused by the next workgroup
-            }
+            for (unsigned y = 0; y < gy; ++y)
+                for (unsigned x = 0; x < gx; ++x) {
+                    blockIdx.x = x;
+                    blockIdx.y = y;
+                    threadIdx.x = t;
+                    kernel();
+                    pthread_barrier_wait(&barrier);  // the shared LDS image is reused by the next workgroup
+                }
         });
     for (auto &th : pool) th.join();
     emu_block_barrier = nullptr;
@@ -210,11 +211,11 @@ int main(int argc, char **argv)
                 const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
                 const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
                 if (tb.gather_tile_tensors <= kGatherFewTensors && !lds_max) {
-                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), [&] {
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
                                k_gather_batched<NT_, kGatherFewTensors>(tb, rp, full, r0, nr);
                            }));
                 } else {
-                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), [&] {
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
                                k_gather_batched<NT_, kGatherMaxTensors>(tb, rp, full, r0, nr);
                            }));
                 }
@@ -252,8 +253,9 @@ int main(int argc, char **argv)
                                  run_grid(TPB_, gx_for((S >> 2) + 1, TPB_ * U_, cap, remap), nr,
                                           [&] { k_reset_flat<TPB_, U_, NT_>(rp, S, N, r0, remap); }));
                 } else {
-                    const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
-                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap),
+                    const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>((nr + rg - 1) / rg);
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups,
                                                      [&] { k_reset_batched<RG_, NT_>(tb, rp, r0, nr); }));
                 }
             } else if (flat) {
@@ -267,9 +269,10 @@ int main(int argc, char **argv)
                 else EMU_ACC_FLAT(false, false, nt);
 #undef EMU_ACC_FLAT
             } else {
-                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
+                const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>((nr + rg - 1) / rg);
 #define EMU_ACC_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                   \
-    EMU_RG(rg, NTF, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {               \
+    EMU_RG(rg, NTF, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {               \
                k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_>(tb, rp, grad, r0, nr, weight);         \
            }))
                 if (atomic && weighted) EMU_ACC_BATCHED(true, true, 0);
@@ -326,12 +329,13 @@ int main(int argc, char **argv)
                 if (atomic) EMU_K(run_grid(64, gx, nr, [&] { k_accum_multi_flat<K_, true>(rp, gp, S, N, r0); }));
                 else EMU_K(run_grid(64, gx, nr, [&] { k_accum_multi_flat<K_, false>(rp, gp, S, N, r0); }));
             } else {
-                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
-                const unsigned gx = grid_x_for(work, 1, cap);
+                const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>(nr);
+                const unsigned gx = grid_x_for(tiles, 1, cap);
                 if (atomic)
-                    EMU_K(run_grid_threaded(kBatchThreads, gx, [&] { k_accum_multi_batched<K_, true>(tb, rp, gp, r0, nr); }));
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, true>(tb, rp, gp, r0, nr); }));
                 else
-                    EMU_K(run_grid_threaded(kBatchThreads, gx, [&] { k_accum_multi_batched<K_, false>(tb, rp, gp, r0, nr); }));
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, false>(tb, rp, gp, r0, nr); }));
             }
         }
 #undef EMU_K
@@ -383,8 +387,9 @@ int main(int argc, char **argv)
                                    k_stage_push_flat<NT_>(rs, g, flags, S, N, slot, R, r0, worker);
                                }));
                     } else {
-                        const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
-                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                        const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>(nr);
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
                                    k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, nr, worker);
                                }));
                     }
@@ -405,8 +410,9 @@ int main(int argc, char **argv)
                                    k_stage_drain_flat<NT_>(ra, rs, snap, S, N, slot, R, r0);
                                }));
                     } else {
-                        const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * nr;
-                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                        const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>(nr);
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
                                    k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0, nr);
                                }));
                     }
@@ -457,13 +463,14 @@ int main(int argc, char **argv)
                                  }));
                 }
             } else {
-                const int64_t work = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift) * ((nr + rg - 1) / rg);
+                const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                const unsigned groups = static_cast<unsigned>((nr + rg - 1) / rg);
                 if (bf16) {
-                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
                                k_retrieve_batched<RG_, NT_, true>(tb, ra, ro, r0, nr, scale);
                            }));
                 } else {
-                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(work, 1, cap), [&] {
+                    EMU_RG(rg, nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
                                k_retrieve_batched<RG_, NT_, false>(tb, ra, ro, r0, nr, scale);
                            }));
                 }
