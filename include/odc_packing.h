@@ -45,6 +45,10 @@ int odc_kk_partition(const int64_t *costs, int n, int k, int equal_size, int *pa
  *            its own microbatch count until every microbatch has at most max_tokens tokens.
  *   mode 1 = LB-Micro: equal sample counts (n % world must be 0) and one common microbatch
  *            count, raised until no device has an infeasible microbatch.
+ *   mode 2 = LocalSort (the unpacked baseline of Section 5.1): the samples are dealt to the
+ *            devices in the order given, n / world each (n % world must be 0); every device
+ *            sorts its own by length, longest first, and runs one sample per microbatch.
+ *            max_tokens is not used.
  *   device_of [n] out, micro_of [n] out: device and microbatch (index within the device) of
  *            every sample; micro_count [world] out: microbatches per device (empty ones are
  *            not counted in LB-Mini; LB-Micro counts the common k on every device).

@@ -28,6 +28,10 @@ get_compute_costs and check_oom are not printed; the readings taken here:
     count exceeds `max_tokens` (a single sample longer than the cap cannot be split, so it is
     accepted alone).  parity unpinned.
 
+  * LocalSort (Section 5.1 says only: sorted by length within each device's minibatch, not
+    packed): samples dealt in order, n / world per device, longest first, one per microbatch.
+    The sort direction does not change either runtime estimate.
+
 All arithmetic is exact Python integer arithmetic.
 """
 from __future__ import annotations
@@ -141,6 +145,21 @@ def lb_micro(seqlens: Sequence[int], world: int, max_tokens: int, hidden: int = 
         if not bad or k >= n_max:
             return [[[part[j] for j in mb] for mb in parts] for part, parts in zip(device_parts, per_device)]
         k += 1
+
+
+def local_sort(seqlens: Sequence[int], world: int):
+    """LocalSort (Section 5.1): no balancing and no packing -- the minibatch is dealt to the
+    devices in the order given, each device sorts its samples by length (longest first, ties by
+    index) and runs one sample per microbatch."""
+    n = len(seqlens)
+    if n % world != 0:
+        raise ValueError("LocalSort needs len(seqlens) to be a multiple of world")
+    per = n // world
+    plan = []
+    for d in range(world):
+        ids = sorted(range(d * per, (d + 1) * per), key=lambda i: (-seqlens[i], i))
+        plan.append([[i] for i in ids])
+    return plan
 
 
 def runtimes(seqlens: Sequence[int], plan, hidden: int = 0) -> Tuple[int, int, List[int]]:

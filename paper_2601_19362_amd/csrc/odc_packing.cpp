@@ -185,14 +185,31 @@ int odc_plan_minibatch(const int64_t *seqlens, int n, int world, int64_t max_tok
                        int *device_of, int *micro_of, int *micro_count)
 {
     if (!seqlens || !device_of || !micro_of || !micro_count || n < 1 || world < 1 || max_tokens < 1 ||
-        hidden < 0 || (mode != 0 && mode != 1))
+        hidden < 0 || mode < 0 || mode > 2)
         return ODC_ERR_INVALID_ARG;
-    if (mode == 1 && n % world != 0) return ODC_ERR_INVALID_ARG;
+    if (mode != 0 && n % world != 0) return ODC_ERR_INVALID_ARG;
     try {
         std::vector<int> all(static_cast<size_t>(n));
         for (int i = 0; i < n; ++i) {
             if (seqlens[i] < 0) return ODC_ERR_INVALID_ARG;
             all[static_cast<size_t>(i)] = i;
+        }
+        if (mode == 2) {
+            // LocalSort: the minibatch is dealt to the devices in the order given; each device
+            // sorts its samples by length (longest first, ties by index) and runs them one per
+            // microbatch.  No balancing, no packing.
+            const int per_device = n / world;
+            for (int d = 0; d < world; ++d) {
+                std::vector<int> ids(all.begin() + static_cast<std::ptrdiff_t>(d) * per_device,
+                                     all.begin() + static_cast<std::ptrdiff_t>(d + 1) * per_device);
+                std::stable_sort(ids.begin(), ids.end(), [&](int a, int b) { return seqlens[a] > seqlens[b]; });
+                for (int m = 0; m < per_device; ++m) {
+                    device_of[ids[static_cast<size_t>(m)]] = d;
+                    micro_of[ids[static_cast<size_t>(m)]] = m;
+                }
+                micro_count[d] = per_device;
+            }
+            return ODC_OK;
         }
         std::vector<int64_t> costs;
         int rc = costs_of(seqlens, all, hidden, &costs);

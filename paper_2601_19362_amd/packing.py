@@ -11,6 +11,7 @@ from . import binding
 
 LB_MINI = 0
 LB_MICRO = 1
+LOCAL_SORT = 2
 EXPORTS = ("odc_compute_cost", "odc_kk_partition", "odc_plan_minibatch", "odc_plan_runtime")
 
 _i64 = ctypes.c_int64

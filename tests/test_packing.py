@@ -141,6 +141,32 @@ def test_cost_model_and_plans_by_hand():
             assert sum(seq[i] for i in mb) <= 10
 
 
+def test_local_sort_by_hand():
+    """LocalSort: dealt in order, sorted inside the device, one sample per microbatch.
+    2 devices: device 0 gets lengths (3, 9, 5) -> 9, 5, 3; device 1 gets (4, 4, 10) -> 10, 4, 4."""
+    seq = [3, 9, 5, 4, 4, 10]
+    plan = po.local_sort(seq, 2)
+    assert plan == [[[1], [2], [0]], [[5], [3], [4]]]
+    t_coll, t_odc, busy = po.runtimes(seq, plan)
+    assert busy == [81 + 25 + 9, 100 + 16 + 16]
+    assert t_coll == 100 + 25 + 16                    # per step the longer of the two
+    assert t_odc == 132
+    with pytest.raises(ValueError):
+        po.local_sort(seq, 4)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_balancing_beats_local_sort(seed):
+    """On long-tailed lengths both balanced plans finish a minibatch sooner than LocalSort under
+    the scheme they are meant for (collectives for LB-Micro, ODC for LB-Mini)."""
+    seq = lengths(64, 50 + seed)
+    ls = po.runtimes(seq, po.local_sort(seq, 8), 3584)
+    micro = po.runtimes(seq, po.lb_micro(seq, 8, 32768, 3584), 3584)
+    mini = po.runtimes(seq, po.lb_mini(seq, 8, 32768, 3584), 3584)
+    assert micro[0] <= ls[0]
+    assert mini[1] <= ls[1]
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_lb_mini_never_slower_than_lb_micro_under_odc(seed):
     """What Section 4 claims for LB-Mini: balancing whole minibatches is at least as good as
@@ -185,7 +211,8 @@ def test_native_kk_equals_oracle(n, k, equal):
                                                 (128, 16, 16384, 3584), (256, 32, 32768, 5120), (64, 8, 1000, 0)])
 def test_native_plans_and_runtime_equal_oracle(n, world, cap, hidden):
     seq = [8, 6, 4, 2] if n == 4 else lengths(n, n + world)
-    for mode, fn in ((packing.LB_MINI, po.lb_mini), (packing.LB_MICRO, po.lb_micro)):
+    for mode, fn in ((packing.LB_MINI, po.lb_mini), (packing.LB_MICRO, po.lb_micro),
+                     (packing.LOCAL_SORT, lambda s, w, c, h: po.local_sort(s, w))):
         plan, counts = packing.plan_minibatch(seq, world, cap, hidden, mode)
         want = fn(seq, world, cap, hidden)
         assert plan == want
@@ -217,4 +244,31 @@ def test_native_argument_errors():
     cnt = (ctypes.c_int * 2)()
     assert lib.odc_plan_minibatch(arr, 4, 2, 0, 0, 0, out, out, cnt) == odc.ODC_ERR_INVALID_ARG   # cap < 1
     assert lib.odc_plan_minibatch(arr, 4, 3, 10, 0, 1, out, out, cnt) == odc.ODC_ERR_INVALID_ARG  # LB-Micro 4 % 3
-    assert lib.odc_plan_minibatch(arr, 4, 2, 10, 0, 2, out, out, cnt) == odc.ODC_ERR_INVALID_ARG  # bad mode
+    assert lib.odc_plan_minibatch(arr, 4, 3, 10, 0, 2, out, out, cnt) == odc.ODC_ERR_INVALID_ARG  # LocalSort 4 % 3
+    assert lib.odc_plan_minibatch(arr, 4, 2, 10, 0, 3, out, out, cnt) == odc.ODC_ERR_INVALID_ARG  # bad mode
+
+
+def test_bubble_table_estimates():
+    """The bubble-rate table: ODC is never slower than collectives for the same plan (a maximum
+    of sums against a sum of maxima), Collective + LocalSort is the unit, LB-Mini exists only
+    under ODC, and every figure equals what the oracle gives for the same minibatches."""
+    from paper_2601_19362_amd import bubble_table as bt
+    table = bt.estimate(world=4, samples_per_device=4, minibatches=6, max_tokens=16384, hidden=1536, seed=3)
+    assert set(table) == {("Collective", "LocalSort"), ("Collective", "LB-Micro"), ("ODC", "LocalSort"),
+                          ("ODC", "LB-Micro"), ("ODC", "LB-Mini")}
+    assert table[("Collective", "LocalSort")][0] == pytest.approx(1.0)
+    for name in ("LocalSort", "LB-Micro"):
+        assert table[("ODC", name)][0] <= table[("Collective", name)][0] + 1e-12
+        assert table[("ODC", name)][1] <= table[("Collective", name)][1] + 1e-12
+    for t, bub in table.values():
+        assert t > 0 and 0.0 <= bub < 1.0
+    # the same six minibatches through the oracle
+    rel, bubbles = [], []
+    for b in range(6):
+        seq = bt.synthetic_lengths(16, 3 * 100003 + b, 7.0, 1.0, 128, 32768)
+        base = po.runtimes(seq, po.local_sort(seq, 4), 1536)[0]
+        t_coll, t_odc, busy = po.runtimes(seq, po.lb_mini(seq, 4, 16384, 1536), 1536)
+        rel.append(t_odc / base)
+        bubbles.append(po.bubble_rate(t_odc, busy))
+    assert table[("ODC", "LB-Mini")][0] == pytest.approx(np.mean(rel), rel=1e-12)
+    assert table[("ODC", "LB-Mini")][1] == pytest.approx(np.mean(bubbles), rel=1e-12)
