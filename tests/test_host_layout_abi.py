@@ -166,3 +166,21 @@ def test_probe_and_tune_argument_errors():
                         (b"gather_unroll", 1), (b"accum_unroll", 2), (b"reset_unroll", 4),
                         (b"nontemporal", 0), (b"tile_remap", 1), (b"gather_store_sc1", 0), (b"max_grid_x", 512), (b"defaults", 0)]:
         assert lib.odc_tune(knob, value) == 0
+
+
+def test_headers_compile_as_plain_c_and_cxx(tmp_path):
+    """The boundary is a C ABI: both headers must be usable from a C99 translation unit (and
+    from C++) with warnings as errors."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "odc.h"\n#include "odc_packing.h"\n'
+                   'int main(void) { return odc_strerror(ODC_OK) == 0 && ODC_MAX_FUSED > 0; }\n')
+    inc = os.path.join(root, "include")
+    if shutil.which("gcc"):
+        subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
+                        str(src)], check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
+                        "-x", "c++", str(src)], check=True)
