@@ -250,8 +250,10 @@ int odc_last_hip_error(void);
  *   "tile_remap"    0 or 1: each XCD sweeps its own contiguous eighth of the tiles
  *   "gather_store_sc1"  0 or 1: single-tensor gather stores carry sc1 + nt instead of nt
  *   "max_grid_x"    0 = one workgroup per tile; > 0 caps the grid, workgroups then loop
- *   "batch_rank_group"  owners handled by one workgroup of the multi-tensor accumulate and
- *                   reset kernels: 0 = chosen from the launch size, or 1, 2, 4, 8
+ *   "batch_rank_group"  owners handled by one workgroup of the multi-tensor accumulate,
+ *                   retrieve and reset kernels: 0 = built-in choice (two for the
+ *                   read-modify-write kernels when the launch is large enough, one for reset
+ *                   and for small launches), or 1, 2, 4, 8
  *   "defaults"      with value 0: every knob back to its built-in default
  * Returns ODC_ERR_INVALID_ARG for an unknown name or a value out of range.  Results never
  * depend on the knobs.
