@@ -284,3 +284,9 @@ def test_7b_layer_staging_and_fused(oracle):
     for r in range(R):
         assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"staged + fused accumulate rank {r}")
     L.close()
+
+
+def test_single_tensor_beyond_32_bit_indices(oracle):
+    """N = 2^31 + 5 elements, R = 8: flat indices, byte offsets and work-item counts all pass
+    2^31 / 2^32; an index computed in 32 bits anywhere in the flat kernels would show here."""
+    full_layer_case(oracle, (1 << 31) + 5, 8, [(0, 0), (7, 1)], seed=77)
