@@ -290,3 +290,41 @@ def test_single_tensor_beyond_32_bit_indices(oracle):
     """N = 2^31 + 5 elements, R = 8: flat indices, byte offsets and work-item counts all pass
     2^31 / 2^32; an index computed in 32 bits anywhere in the flat kernels would show here."""
     full_layer_case(oracle, (1 << 31) + 5, 8, [(0, 0), (7, 1)], seed=77)
+
+
+def test_beyond_32_bit_indices_fused_unordered_and_retrieve(oracle):
+    """The same size through the fused entry point (ordered), one unordered contribution and
+    both retrievals.  Gradients are small integers, so every sum is exact and the unordered
+    result must equal the ordered oracle bit for bit."""
+    N, R = (1 << 31) + 5, 8
+    print(f"beyond-32-bit fused/retrieve case N={N} R={R}", flush=True)
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    acc = [torch.full((S,), 3.25, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc_h = [np.full(S, 3.25, dtype=np.float32) for _ in range(R)]
+    L.reset_accum(acc)
+    oracle.reset(acc_h, N, nthreads=THREADS)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    grads = [torch.randint(-200, 201, (N,), generator=gen, device=dev, dtype=torch.int16).to(torch.bfloat16)
+             for _ in range(3)]
+    L.scatter_accumulate_multi(grads[:2], acc, [0, 0], [0, 1])
+    L.scatter_accumulate(grads[2], acc, 0, 0, odc.ODC_UNORDERED)
+    for g in grads:
+        oracle.accumulate(g.view(torch.int16).cpu().numpy().view(np.uint16), acc_h, N, nthreads=THREADS)
+    torch.cuda.synchronize()
+    del grads
+    for r in range(R):
+        assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"fused + unordered accumulate rank {r}")
+    scale = 1.0 / 3.0
+    for bf16 in (False, True):
+        out = [torch.zeros(S, dtype=torch.int16 if bf16 else torch.float32, device=dev) for _ in range(R)]
+        want = [np.zeros(S, dtype=np.uint16 if bf16 else np.float32) for _ in range(R)]
+        L.retrieve_grads(acc, out, scale, odc.ODC_OUT_BF16 if bf16 else odc.ODC_OUT_F32)
+        oracle.retrieve(acc_h, want, N, scale=scale, nthreads=THREADS)
+        for r in range(R):
+            got = out[r].cpu().numpy()
+            assert_bits_equal(got.view(np.uint16) if bf16 else got, want[r], f"retrieve bf16={bf16} rank {r}")
+        del out
+    L.close()
