@@ -77,6 +77,7 @@ int upload_table(odc_layout_t *L)
     L->table.spread = reinterpret_cast<const int32_t *>(d + desc_bytes + chunk_bytes + full_chunk_bytes);
     L->table.n_spread = static_cast<int32_t>(H.spread.size());
     L->table.gather_tile_tensors = H.gather_tile_tensors;
+    L->table.gather_big = H.gather_big;
     L->table.arena_elems = H.arena_elems;
     L->table.full_elems = H.full_elems;
     L->table.T = H.T;

@@ -423,6 +423,18 @@ __device__ __forceinline__ int valid_from(const TensorDesc &d, int r, int64_t sl
     return left >= width ? width : (left > 0 ? static_cast<int>(left) : 0);
 }
 
+// True when the arena tile that starts at element a0 lies wholly inside the slots of tensor d
+// that are valid for every owner in [r_first, r_first + count).  Every item of such a tile is
+// a full vector of one tensor, so the kernels skip the per-item lookup and validity checks and
+// run the same lean loop as the single-tensor kernels (large tensors of a multi-tensor layout,
+// e.g. a decoder layer kept as separate weight matrices, then move at nearly the same rate).
+__device__ __forceinline__ bool tile_is_uniform(const TensorDesc &d, int64_t a0, int r_first, int count)
+{
+    int64_t valid = d.numel - static_cast<int64_t>(r_first + count - 1) * d.S;  // the last owner has the fewest
+    if (valid > d.S) valid = d.S;
+    return a0 >= d.shard_off && a0 - d.shard_off + kChunkElems <= valid;
+}
+
 // ---- gather, full-buffer-major ---------------------------------------------------------
 // Per-tensor record of the gather kernel, staged in LDS once per tile.  Offsets are 32-bit
 // and relative to the tile so that the per-item index arithmetic stays in 32-bit integer
@@ -599,7 +611,7 @@ __device__ __forceinline__ int gather_find(const GatherTile<CAP> &lds, int n, in
 // at the rate the number of resident wavefronts allows, so everything rare is kept out of
 // the main path -- tensors with S < 8 (an item spans three or more owners) are skipped here
 // and copied element-wise, one lane per element, by the loop at the end of the kernel.
-template <bool NT, int CAP>
+template <bool NT, int CAP, bool BIG>
 __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
                                                                   uint16_t *__restrict__ full, int r0, int nr)
 {
@@ -616,6 +628,35 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
         const int64_t a0 = c0 << kChunkShift;
         const int t_lo = tb.full_chunk_first[c0];
         const int n = tb.full_chunk_first[c1] - t_lo + 1;  // <= CAP: the launcher picked CAP
+        if (BIG && n == 1) {
+            // A tile that lies inside one owner's piece of one tensor (most tiles of a large
+            // tensor, whatever its size): a plain copy with uniform source and destination,
+            // no staging, no per-item arithmetic.  (BIG: the layout has a tensor whose shard
+            // pieces are at least a tile long; layouts of small tensors only run the variant
+            // without this path, which is a few per cent faster for them.)
+            const TensorDesc d = tb.desc[t_lo];
+            constexpr int64_t kTile = static_cast<int64_t>(kGatherChunks) * kChunkElems;
+            const int64_t j0 = a0 - d.full_off;
+            if (j0 >= 0 && j0 + kTile <= d.numel) {
+                const int64_t r = div_owner64(j0, d.S);
+                const int64_t i0 = j0 - r * d.S;
+                if (i0 + kTile <= d.S && r >= r0 && r < r0 + nr) {
+                    const uint16_t *src = static_cast<const uint16_t *>(arenas.p[r - r0]) + d.shard_off + i0;
+                    uint16_t *dst = full + a0;
+#pragma unroll 1
+                    for (int grp = 0; grp < kGatherChunks / UG; ++grp) {
+                        u32x4 v[UG];
+#pragma unroll
+                        for (int u = 0; u < UG; ++u)
+                            v[u] = ld_u128_unaligned<NT>(src + 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x)));
+#pragma unroll
+                        for (int u = 0; u < UG; ++u)
+                            st<NT>(reinterpret_cast<u32x4 *>(dst) + (grp * UG + u) * kBatchThreads + threadIdx.x, v[u]);
+                    }
+                    continue;
+                }
+            }
+        }
         for (int k = threadIdx.x; k < n; k += kBatchThreads) {
             const GatherRec g = make_gather_rec(tb.desc[t_lo + k], a0);
             lds.rel[k] = g.rel;
@@ -776,7 +817,7 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap,
 // chip works on a few advancing address windows at a time (measurably faster than spreading
 // every tile over all owners first); and no kernel has to divide a linear work index.
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
-__global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 1) void k_accum_batched(BatchTable tb, RankPtrs accs,
+__global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG == 2 ? 8 : 1) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
                                                                  float w)
 {
@@ -818,6 +859,29 @@ __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG <= 2 ? 8 : 1) vo
                                         WEIGHTED ? w * widen_one(gv[u][k]) : widen_one(gv[u][k]));
             }
         } else {
+            if constexpr (RG == 1) {
+                // (only the one-owner variant, which is the one picked for layouts of large
+                // tensors: with more owners per workgroup the extra path costs registers)
+                if (n == 1 && rl0 < nr && tile_is_uniform(tb.desc[t_lo], tile << kChunkShift, r0 + rl0, 1)) {
+                    const TensorDesc d = tb.desc[t_lo];
+                    float *arena = static_cast<float *>(accs.p[rl0]);
+                    const uint16_t *g = grad + d.full_off + static_cast<int64_t>(r0 + rl0) * d.S - d.shard_off;
+                    u32x2 gv[kAccumItems];
+                    f32x4 av[kAccumItems];
+#pragma unroll
+                    for (int u = 0; u < kAccumItems; ++u) {
+                        const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+                        gv[u] = ld_u64_unaligned<NT>(g + a);
+                        av[u] = ld<NT>(reinterpret_cast<const f32x4 *>(arena + a));
+                    }
+#pragma unroll
+                    for (int u = 0; u < kAccumItems; ++u) {
+                        const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+                        st<NT>(reinterpret_cast<f32x4 *>(arena + a), add4<WEIGHTED>(av[u], gv[u], w));
+                    }
+                    continue;
+                }
+            }
             AccumItem items[kAccumItems][RG];
 #pragma unroll
             for (int u = 0; u < kAccumItems; ++u) {
@@ -858,6 +922,18 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
         if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
+        const int owners = nr - rl0 < RG ? nr - rl0 : RG;
+        if (n == 1 && tile_is_uniform(tb.desc[t_lo], tile << kChunkShift, r0 + rl0, owners)) {
+#pragma unroll
+            for (int u = 0; u < kAccumItems; ++u) {
+                const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+#pragma unroll
+                for (int k = 0; k < RG; ++k)
+                    if (k < owners)
+                        st_stream<NT ? 2 : 0>(reinterpret_cast<f32x4 *>(static_cast<float *>(accs.p[rl0 + k]) + a), zero);
+            }
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {
             const int a_rel = 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
@@ -980,7 +1056,7 @@ __global__ __launch_bounds__(64) void k_accum_multi_flat(RankPtrs accs, GradPtrs
 // Batched form: grid x = tiles of the rank arena, y = owners.
 template <int K, bool ATOMIC>
 __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTable tb, RankPtrs accs, GradPtrs grads,
-                                                                       int r0, int nr)
+                                                                       int r0)
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
@@ -1083,7 +1159,7 @@ template <bool NT>
 __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable tb, RankPtrs staging,
                                                                       const uint16_t *__restrict__ grad,
                                                                       const int32_t *__restrict__ flags,
-                                                                      int64_t slot, int R, int r0, int nr, int worker)
+                                                                      int64_t slot, int R, int r0, int worker)
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
@@ -1223,7 +1299,7 @@ __global__ __launch_bounds__(64) void k_stage_drain_flat(RankPtrs accs, RankPtrs
 template <bool NT>
 __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTable tb, RankPtrs accs, RankPtrs staging,
                                                                        const int32_t *__restrict__ snapshot,
-                                                                       int64_t slot, int R, int r0, int nr)
+                                                                       int64_t slot, int R, int r0)
 {
     __shared__ TileIndex<1> lds;
     const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
@@ -1339,6 +1415,33 @@ __global__ __launch_bounds__(kBatchThreads) void k_retrieve_batched(BatchTable t
         int t_lo, n;
         stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
         f32x4 v[kAccumItems][RG];
+        const int owners = nr - rl0 < RG ? nr - rl0 : RG;
+        if (n == 1 && tile_is_uniform(tb.desc[t_lo], tile << kChunkShift, r0 + rl0, owners)) {
+#pragma unroll
+            for (int u = 0; u < kAccumItems; ++u) {
+                const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+#pragma unroll
+                for (int k = 0; k < RG; ++k)
+                    if (k < owners) v[u][k] = ld<NT>(reinterpret_cast<const f32x4 *>(static_cast<const float *>(accs.p[rl0 + k]) + a));
+            }
+#pragma unroll
+            for (int u = 0; u < kAccumItems; ++u) {
+                const int64_t a = (tile << kChunkShift) + 4 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+#pragma unroll
+                for (int k = 0; k < RG; ++k) {
+                    if (k >= owners) continue;
+                    const f32x4 sv = {scale * v[u][k].x, scale * v[u][k].y, scale * v[u][k].z, scale * v[u][k].w};
+                    if constexpr (BF16) {
+                        const u32x2 p = {narrow_bf16(sv.x) | (narrow_bf16(sv.y) << 16),
+                                         narrow_bf16(sv.z) | (narrow_bf16(sv.w) << 16)};
+                        st_stream<NT ? 2 : 0>(reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outs.p[rl0 + k]) + a), p);
+                    } else {
+                        st_stream<NT ? 2 : 0>(reinterpret_cast<f32x4 *>(static_cast<float *>(outs.p[rl0 + k]) + a), sv);
+                    }
+                }
+            }
+            continue;
+        }
         int cnt[kAccumItems][RG];
 #pragma unroll
         for (int u = 0; u < kAccumItems; ++u) {

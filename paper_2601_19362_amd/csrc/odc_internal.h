@@ -49,6 +49,7 @@ struct BatchTable {
     int32_t T;
     int32_t n_spread;
     int32_t gather_tile_tensors;      // most tensors that intersect one gather tile
+    int32_t gather_big;               // 1: some tensor's shard pieces are at least one gather tile long
 };
 
 struct HostLayout {
@@ -62,6 +63,7 @@ struct HostLayout {
     std::vector<int32_t> full_chunk_first;  // built for T > 1
     std::vector<int32_t> spread;            // built for T > 1: tensors with S < kAlignElems
     int gather_tile_tensors = 1;            // built for T > 1
+    int gather_big = 0;                     // built for T > 1
 };
 
 // Pure integer layout construction (Section 3.1 even partition, tail padding).

@@ -120,11 +120,14 @@ static unsigned batched_grid_x(int64_t tiles)
 
 // Owners per workgroup in the batched accumulate / reset / retrieve kernels.  A workgroup that
 // serves two owners looks its tensors up once for both, which pays for the read-modify-write
-// kernels when there is enough work to fill the chip; the write-only reset is fastest with one.
-static int rank_group(int64_t tiles, int nr, int preferred)
+// kernels on layouts of many small tensors when there is enough work to fill the chip; the
+// write-only reset, and layouts whose shard pieces are long (mean of 1024 elements or more:
+// most tiles then lie inside one tensor and take the lean path), are fastest with one.
+static int rank_group(const BatchTable &tb, int64_t tiles, int nr, int preferred)
 {
     const int forced = tuning().batch_rank_group;
     if (forced > 0) return forced;
+    if (tb.arena_elems / tb.T >= 1024) return 1;
     for (int rg = preferred; rg > 1; rg >>= 1)
         if (tiles * ((nr + rg - 1) / rg) >= 4096) return rg;
     return 1;
@@ -147,15 +150,17 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
-    if (tb.gather_tile_tensors <= kGatherFewTensors) {
-        ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                        (k_gather_batched<NT_, kGatherFewTensors><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
-                            tb, rp, static_cast<uint16_t *>(full), r0, nr)));
-    } else {
-        ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                        (k_gather_batched<NT_, kGatherMaxTensors><<<dim3(batched_grid_x(tiles)), kBatchThreads, 0, s>>>(
-                            tb, rp, static_cast<uint16_t *>(full), r0, nr)));
-    }
+    const dim3 grid(batched_grid_x(tiles));
+    uint16_t *out = static_cast<uint16_t *>(full);
+#define ODC_GATHER_BATCHED(CAP_, BIG_)                                 \
+    ODC_DISPATCH_NT(tuning().nontemporal != 0,                         \
+                    (k_gather_batched<NT_, CAP_, BIG_><<<grid, kBatchThreads, 0, s>>>(tb, rp, out, r0, nr)))
+    const bool few = tb.gather_tile_tensors <= kGatherFewTensors;
+    if (few && tb.gather_big) ODC_GATHER_BATCHED(kGatherFewTensors, true);
+    else if (few) ODC_GATHER_BATCHED(kGatherFewTensors, false);
+    else if (tb.gather_big) ODC_GATHER_BATCHED(kGatherMaxTensors, true);
+    else ODC_GATHER_BATCHED(kGatherMaxTensors, false);
+#undef ODC_GATHER_BATCHED
     return finish();
 }
 
@@ -166,7 +171,7 @@ int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr, 2);
+    const int rg = rank_group(tb, tiles, nr, 2);
     const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
 #define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                     \
     ODC_DISPATCH_RG(rg, NTF,                                                                           \
@@ -185,7 +190,7 @@ int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr, 1);
+    const int rg = rank_group(tb, tiles, nr, 1);
     const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
     ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
                     (k_reset_batched<RG_, NT_><<<grid, kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
@@ -232,9 +237,9 @@ int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     if (atomic)
-        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, true><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0, nr)));
+        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, true><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0)));
     else
-        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, false><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0, nr)));
+        ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, false><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0)));
     return finish();
 }
 
@@ -266,7 +271,7 @@ int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0
     ODC_DISPATCH_NT(tuning().nontemporal != 0,
                     (k_stage_push_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,
-                        nr, worker)));
+                        worker)));
     return finish();
 }
 
@@ -312,7 +317,7 @@ int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const vo
     const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     ODC_DISPATCH_NT(tuning().nontemporal != 0,
                     (k_stage_drain_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
-                        tb, ra, rs, static_cast<const int32_t *>(snapshot), slot, R, r0, nr)));
+                        tb, ra, rs, static_cast<const int32_t *>(snapshot), slot, R, r0)));
     return finish();
 }
 
@@ -342,7 +347,7 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
     const RankPtrs ro = pack(out, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tiles, nr, 2);
+    const int rg = rank_group(tb, tiles, nr, 2);
     const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
     if (bf16) {
         ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,

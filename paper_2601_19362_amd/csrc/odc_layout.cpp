@@ -94,8 +94,11 @@ int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out)
         // What the batched gather kernel needs beyond the indices: the tensors it copies
         // element-wise, and the most tensors any of its tiles holds (sizes its LDS staging).
         try {
-            for (int t = 0; t < T; ++t)
-                if (L.desc[static_cast<size_t>(t)].S < kAlignElems) L.spread.push_back(t);
+            for (int t = 0; t < T; ++t) {
+                const int64_t S = L.desc[static_cast<size_t>(t)].S;
+                if (S < kAlignElems) L.spread.push_back(t);
+                if (S >= (int64_t{kGatherChunks} << kChunkShift)) L.gather_big = 1;
+            }
         } catch (...) {
             return ODC_ERR_NOMEM;
         }

@@ -181,7 +181,7 @@ int main(int argc, char **argv)
     }
     const size_t arena = static_cast<size_t>(H.arena_elems), full_n = static_cast<size_t>(H.full_elems);
     BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.spread.data(), H.arena_elems,
-                  H.full_elems, H.T, static_cast<int32_t>(H.spread.size()), H.gather_tile_tensors};
+                  H.full_elems, H.T, static_cast<int32_t>(H.spread.size()), H.gather_tile_tensors, H.gather_big};
     const bool flat = H.T == 1;
     const int64_t S = H.desc[0].S, N = H.desc[0].numel;
 
@@ -212,11 +212,13 @@ int main(int argc, char **argv)
                 const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
                 if (tb.gather_tile_tensors <= kGatherFewTensors && !lds_max) {
                     EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
-                               k_gather_batched<NT_, kGatherFewTensors>(tb, rp, full, r0, nr);
+                               if (tb.gather_big) k_gather_batched<NT_, kGatherFewTensors, true>(tb, rp, full, r0, nr);
+                               else k_gather_batched<NT_, kGatherFewTensors, false>(tb, rp, full, r0, nr);
                            }));
                 } else {
                     EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
-                               k_gather_batched<NT_, kGatherMaxTensors>(tb, rp, full, r0, nr);
+                               if (tb.gather_big) k_gather_batched<NT_, kGatherMaxTensors, true>(tb, rp, full, r0, nr);
+                               else k_gather_batched<NT_, kGatherMaxTensors, false>(tb, rp, full, r0, nr);
                            }));
                 }
             }
@@ -333,9 +335,9 @@ int main(int argc, char **argv)
                 const unsigned groups = static_cast<unsigned>(nr);
                 const unsigned gx = grid_x_for(tiles, 1, cap);
                 if (atomic)
-                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, true>(tb, rp, gp, r0, nr); }));
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, true>(tb, rp, gp, r0); }));
                 else
-                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, false>(tb, rp, gp, r0, nr); }));
+                    EMU_K(run_grid_threaded(kBatchThreads, gx, groups, [&] { k_accum_multi_batched<K_, false>(tb, rp, gp, r0); }));
             }
         }
 #undef EMU_K
@@ -390,7 +392,7 @@ int main(int argc, char **argv)
                         const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
                 const unsigned groups = static_cast<unsigned>(nr);
                         EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
-                                   k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, nr, worker);
+                                   k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, worker);
                                }));
                     }
                 }
@@ -413,7 +415,7 @@ int main(int argc, char **argv)
                         const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
                 const unsigned groups = static_cast<unsigned>(nr);
                         EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
-                                   k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0, nr);
+                                   k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0);
                                }));
                     }
                 }

@@ -100,6 +100,8 @@ CASES = [
     ([1] * 1100 + [20000, 2], 2),     # a gather tile whose LDS index is filled to the brim
     ([1300, 2000, 1043, 520, 8 * 130], 130),  # S = 10, 16, 9, 4, 8 over three launch groups: items
                                               # that straddle two owners of different launches
+    ([100_000, 9, 50_001, 3], 2),     # shard pieces of 50,000 and 25,001 elements: whole tiles inside
+                                      # one owner's piece of one tensor (the lean uniform-tile paths)
 ]
 
 
