@@ -328,3 +328,54 @@ def test_beyond_32_bit_indices_fused_unordered_and_retrieve(oracle):
             assert_bits_equal(got.view(np.uint16) if bf16 else got, want[r], f"retrieve bf16={bf16} rank {r}")
         del out
     L.close()
+
+
+def test_7b_layer_as_nine_tensors(oracle):
+    """The 7B decoder layer kept as nine separate tensors (q, k, v, o, gate, up, down and two
+    norm vectors) in one multi-tensor layout: the lean uniform-tile paths of the batched kernels
+    carry almost all of it.  Gather, reset, two contributions and a retrieval, compared in full."""
+    h, ffn, q, kv = 3584, 18944, 28, 4
+    numel = [h * q * 128, h * kv * 128, h * kv * 128, h * q * 128, h * ffn, h * ffn, h * ffn, h, h]
+    R = 16
+    assert sum(numel) == inputs.workload("7b").numel[0]
+    print(f"nine-tensor 7b layer R={R}", flush=True)
+    L = odc.Layout(R, numel)
+    T = len(numel)
+    S = [L.shard_elems(t) for t in range(T)]
+    so = [L.shard_offset(t) for t in range(T)]
+    fo = [L.full_offset(t) for t in range(T)]
+    arena, full_n = L.rank_arena_elems(), L.full_elems()
+    dev = torch.device("cuda")
+    params = [inputs.device_uniform_bf16(arena, -0.05, 0.05, 600 + r, dev) for r in range(R)]
+    full = torch.full((full_n,), 7.0, dtype=torch.bfloat16, device=dev)
+    L.gather(params, full)
+    torch.cuda.synchronize()
+    arenas_h = [p.view(torch.int16).cpu().numpy().view(np.uint16) for p in params]
+    want = np.full(full_n, 0x40E0, dtype=np.uint16)
+    oracle.gather_batched(arenas_h, numel, so, fo, want)
+    assert_bits_equal(full.view(torch.int16).cpu().numpy().view(np.uint16), want, "gather")
+    del params, arenas_h, full, want
+
+    acc = [torch.full((arena,), 3.25, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc_h = [np.full(arena, 3.25, dtype=np.float32) for _ in range(R)]
+    L.reset_accum(acc)
+    oracle.reset_batched(acc_h, numel, so)
+    for k in range(2):
+        g = inputs.device_normal_bf16(full_n, 1e-3, 650 + k, dev)
+        if k == 0:
+            L.scatter_accumulate(g, acc, 3, 0)
+            oracle.accumulate_batched(g.view(torch.int16).cpu().numpy().view(np.uint16), acc_h, numel, so, fo)
+        else:
+            L.scatter_accumulate_weighted(g, acc, 3, 1, 0.37)
+            oracle.accumulate_weighted_batched(g.view(torch.int16).cpu().numpy().view(np.uint16), acc_h, numel, so, fo,
+                                               0.37)
+        del g
+    out = [torch.full((arena,), -1.0, dtype=torch.float32, device=dev) for _ in range(R)]
+    out_h = [np.full(arena, -1.0, dtype=np.float32) for _ in range(R)]
+    L.retrieve_grads(acc, out, 1.0 / 3.0, odc.ODC_OUT_F32)
+    oracle.retrieve_batched(acc_h, out_h, numel, so, scale=1.0 / 3.0)
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert_bits_equal(acc[r].cpu().numpy(), acc_h[r], f"accumulate rank {r}")
+        assert_bits_equal(out[r].cpu().numpy(), out_h[r], f"retrieve rank {r}")
+    L.close()
