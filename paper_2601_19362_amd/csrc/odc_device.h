@@ -643,16 +643,14 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
                 if (i0 + kTile <= d.S && r >= r0 && r < r0 + nr) {
                     const uint16_t *src = static_cast<const uint16_t *>(arenas.p[r - r0]) + d.shard_off + i0;
                     uint16_t *dst = full + a0;
-#pragma unroll 1
-                    for (int grp = 0; grp < kGatherChunks / UG; ++grp) {
-                        u32x4 v[UG];
+                    // all of the thread's items in flight at once: measured best for this path
+                    u32x4 v[kGatherChunks];
 #pragma unroll
-                        for (int u = 0; u < UG; ++u)
-                            v[u] = ld_u128_unaligned<NT>(src + 8 * ((grp * UG + u) * kBatchThreads + static_cast<int>(threadIdx.x)));
+                    for (int u = 0; u < kGatherChunks; ++u)
+                        v[u] = ld_u128_unaligned<NT>(src + 8 * (u * kBatchThreads + static_cast<int>(threadIdx.x)));
 #pragma unroll
-                        for (int u = 0; u < UG; ++u)
-                            st<NT>(reinterpret_cast<u32x4 *>(dst) + (grp * UG + u) * kBatchThreads + threadIdx.x, v[u]);
-                    }
+                    for (int u = 0; u < kGatherChunks; ++u)
+                        st<NT>(reinterpret_cast<u32x4 *>(dst) + u * kBatchThreads + threadIdx.x, v[u]);
                     continue;
                 }
             }
