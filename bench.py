@@ -30,7 +30,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="7b", choices=["tiny", "1.5b", "7b", "32b", "stress"])
+    ap.add_argument("--workload", default="7b", choices=["tiny", "1.5b", "7b", "32b", "stress", "7b-split"])
     ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",

@@ -96,6 +96,14 @@ def decoder_layer_numel(hidden: int, ffn: int, q_heads: int, kv_heads: int) -> i
     return 2 * q + 2 * kv + 3 * hidden * ffn + 2 * hidden
 
 
+def decoder_layer_tensors(hidden: int, ffn: int, q_heads: int, kv_heads: int) -> Tuple[int, ...]:
+    """The same layer kept as separate tensors (per-parameter sharding instead of one flat
+    param): q, k, v, o, gate, up, down, two RMSNorm vectors."""
+    q = hidden * q_heads * HEAD_DIM
+    kv = hidden * kv_heads * HEAD_DIM
+    return (q, kv, kv, q, hidden * ffn, hidden * ffn, hidden * ffn, hidden, hidden)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One synthetic configuration.  `numel` lists the flat params that one layout
@@ -190,6 +198,14 @@ def _cfg_7b() -> Workload:
                     microbatch_rule="longtail")
 
 
+def _cfg_7b_split() -> Workload:
+    """The 7B-shaped workload with every layer kept as nine tensors in one multi-tensor layout
+    (same elements, same ranks, same microbatch counts as "7b")."""
+    return Workload("7b-split", R=16, numel=decoder_layer_tensors(3584, 18944, 28, 4), layers=28, resident_layers=28,
+                    param_range=(-0.05, 0.05), grad_sigma=1e-3, seed=3, microbatch_rule="longtail",
+                    note="per-parameter sharding: nine tensors per layer, batched kernels")
+
+
 def _cfg_32b() -> Workload:
     n = decoder_layer_numel(5120, 27648, 40, 8)
     return Workload("32b", R=32, numel=(n,), layers=64, resident_layers=4,
@@ -206,7 +222,7 @@ def _cfg_stress() -> Workload:
 
 
 _BUILDERS = {"tiny": _cfg_tiny, "1.5b": _cfg_1p5b, "7b": _cfg_7b, "32b": _cfg_32b,
-             "stress": _cfg_stress}
+             "stress": _cfg_stress, "7b-split": _cfg_7b_split}
 WORKLOAD_NAMES = tuple(_BUILDERS)
 
 

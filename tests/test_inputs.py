@@ -64,3 +64,11 @@ def test_microbatch_counts():
     m7 = inputs.microbatch_counts(inputs.workload("7b"))
     assert len(m7) == 16 and all(v >= 1 for v in m7) and len(set(m7)) > 1   # imbalanced
     assert m7 == inputs.microbatch_counts(inputs.workload("7b"))
+
+
+def test_split_layer_workload_matches_the_flat_one():
+    flat, split = inputs.workload("7b"), inputs.workload("7b-split")
+    assert sum(split.numel) == flat.numel[0] and len(split.numel) == 9
+    assert split.numel == inputs.decoder_layer_tensors(3584, 18944, 28, 4)
+    assert (split.R, split.layers) == (flat.R, flat.layers)
+    assert inputs.microbatch_counts(split) == inputs.microbatch_counts(flat)
