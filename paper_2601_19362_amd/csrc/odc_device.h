@@ -351,20 +351,20 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
 }
 
 // --------------------------------------------------------------------------------- batched
-// T tensors in one launch (the many-small-tensor case).  Work is cut into tiles of an index
-// space in which every tensor starts at a multiple of 8 elements:
-//   accumulate / reset walk the owners' rank arenas (the side that is written), so all
-//     writes are dense, aligned 16-byte vectors.  Every owner's arena has the same tensor
-//     placement, so a workgroup takes one tile and a group of RG owners: the tensor of a
-//     work item is looked up once and used for all RG owners, which also puts RG
-//     independent load pairs per item in flight and brings the scattered gradient reads of
-//     the owners of a small tensor close together in time;
+// T tensors in one launch: thousands of small tensors, or a layer kept as a handful of large
+// ones.  Work is cut into tiles of an index space in which every tensor starts at a multiple
+// of 8 elements:
+//   accumulate / reset / retrieve walk the owners' rank arenas (the side that is written),
+//     so all writes are dense, aligned 16-byte vectors.  Every owner's arena has the same
+//     tensor placement, so a workgroup takes one tile and a group of RG owners: the tensor
+//     of a work item is looked up once and used for all RG owners;
 //   gather walks the full buffer (again the side that is written) and pulls each 16-byte
 //     item from the owner that holds it, so the pieces of a small tensor that come from
 //     many owners still leave as full 16-byte stores of one workgroup.
 // The tensors that intersect a tile are staged in LDS once per workgroup (found through the
 // coarse per-chunk index): start offsets for a binary search, and the descriptors themselves.
-// A tile that lies inside one tensor skips all of that.
+// A tile that lies inside one tensor skips all of that, and if all of it is valid for the
+// owners at hand (tile_is_uniform) it runs the plain vector loop of the single-tensor kernels.
 
 constexpr int kChunkElems = 1 << kChunkShift;
 constexpr int kBatchThreads = 256;
