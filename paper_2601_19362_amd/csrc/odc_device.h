@@ -831,6 +831,28 @@ __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG == 2 ? 8 : 1) vo
             // wavefront covers contiguous bytes (see accum_tile_atomic)
             constexpr int E = kChunkElems / kBatchThreads;
             uint16_t gv[E][RG];
+            const int owners = nr - rl0 < RG ? nr - rl0 : RG;
+            if (n == 1 && owners > 0 && tile_is_uniform(tb.desc[t_lo], tile << kChunkShift, r0 + rl0, owners)) {
+                const TensorDesc d = tb.desc[t_lo];
+#pragma unroll
+                for (int u = 0; u < E; ++u) {
+                    const int64_t a = (tile << kChunkShift) + u * kBatchThreads + static_cast<int>(threadIdx.x);
+#pragma unroll
+                    for (int k = 0; k < RG; ++k)
+                        if (k < owners)
+                            gv[u][k] = ld_u16(grad + d.full_off + static_cast<int64_t>(r0 + rl0 + k) * d.S + (a - d.shard_off));
+                }
+#pragma unroll
+                for (int u = 0; u < E; ++u) {
+                    const int64_t a = (tile << kChunkShift) + u * kBatchThreads + static_cast<int>(threadIdx.x);
+#pragma unroll
+                    for (int k = 0; k < RG; ++k)
+                        if (k < owners)
+                            unsafeAtomicAdd(static_cast<float *>(accs.p[rl0 + k]) + a,
+                                            WEIGHTED ? w * widen_one(gv[u][k]) : widen_one(gv[u][k]));
+                }
+                continue;
+            }
             bool on[E][RG];
 #pragma unroll
             for (int u = 0; u < E; ++u) {
