@@ -428,11 +428,12 @@ __device__ __forceinline__ int valid_from(const TensorDesc &d, int r, int64_t sl
 // a full vector of one tensor, so the kernels skip the per-item lookup and validity checks and
 // run the same lean loop as the single-tensor kernels (large tensors of a multi-tensor layout,
 // e.g. a decoder layer kept as separate weight matrices, then move at nearly the same rate).
-__device__ __forceinline__ bool tile_is_uniform(const TensorDesc &d, int64_t a0, int r_first, int count)
+__device__ __forceinline__ bool tile_is_uniform(const TensorDesc &d, int64_t a0, int r_first, int count,
+                                                int tile_elems = kChunkElems)
 {
     int64_t valid = d.numel - static_cast<int64_t>(r_first + count - 1) * d.S;  // the last owner has the fewest
     if (valid > d.S) valid = d.S;
-    return a0 >= d.shard_off && a0 - d.shard_off + kChunkElems <= valid;
+    return a0 >= d.shard_off && a0 - d.shard_off + tile_elems <= valid;
 }
 
 // ---- gather, full-buffer-major ---------------------------------------------------------
@@ -1175,41 +1176,75 @@ __global__ __launch_bounds__(64) void k_stage_push_flat(RankPtrs staging, const 
     copy_to_aligned<64, NT>(grad + base, dst, valid);
 }
 
+// Tiles of kPushChunks chunks: kPushChunks 16-byte items per thread, all loaded before any is
+// stored.
+constexpr int kPushChunks = 2;
+
 template <bool NT>
 __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable tb, RankPtrs staging,
                                                                       const uint16_t *__restrict__ grad,
                                                                       const int32_t *__restrict__ flags,
                                                                       int64_t slot, int R, int r0, int worker)
 {
-    __shared__ TileIndex<1> lds;
-    const int64_t ntiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    __shared__ TileIndex<kPushChunks> lds;
+    constexpr int kTile = kPushChunks * kChunkElems;
+    const int64_t nchunks = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const int64_t ntiles = (nchunks + kPushChunks - 1) / kPushChunks;
     const int rl = static_cast<int>(blockIdx.y);  // grid.y = owners of this launch
+    const int r = r0 + rl;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int r = r0 + rl;
+        const int32_t taken = flags[static_cast<int64_t>(r) * R + worker];  // uniform per workgroup
         int t_lo, n;
-        stage_tile<1>(tb, tile, ntiles, lds, t_lo, n);
-        if (flags[static_cast<int64_t>(r) * R + worker] != 0) continue;  // uniform per workgroup
+        stage_tile<kPushChunks>(tb, tile, nchunks, lds, t_lo, n);
+        if (taken != 0) continue;
         uint16_t *dst = static_cast<uint16_t *>(staging.p[rl]) + static_cast<int64_t>(worker) * slot;
-        const int a_rel = 8 * static_cast<int>(threadIdx.x);
-        const int64_t a = (tile << kChunkShift) + a_rel;
-        if (a >= tb.arena_elems) continue;
-        const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
-        const int64_t slot_in = a - d.shard_off;
-        const int cnt = valid_from(d, r, slot_in, 8);
-        const uint16_t *src = grad + d.full_off + static_cast<int64_t>(r) * d.S + slot_in;
-        if (cnt == 8) {
-            st<NT>(reinterpret_cast<u32x4 *>(dst + a), ld_u128_unaligned<NT>(src));
-        } else if (cnt > 0 && d.full_off + static_cast<int64_t>(r) * d.S + slot_in + 8 <= tb.full_elems) {
-            // ragged end of a shard piece: one wide load (the extra lanes belong to the next
-            // piece and are dropped), element stores
-            const u32x4 v = ld_u128_unaligned<NT>(src);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const int64_t a0 = tile * kTile;
+        u32x4 v[kPushChunks];
+        if (n == 1 && tile_is_uniform(tb.desc[t_lo], a0, r, 1, kTile)) {
+            const TensorDesc d = tb.desc[t_lo];
+            const uint16_t *src = grad + d.full_off + static_cast<int64_t>(r) * d.S - d.shard_off + a0;
 #pragma unroll
-            for (int e = 0; e < 7; ++e)
-                if (e < cnt) st_u16(dst + a + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
-        } else {
-            for (int e = 0; e < cnt; ++e) st_u16(dst + a + e, ld_u16(src + e));
+            for (int u = 0; u < kPushChunks; ++u)
+                v[u] = ld_u128_unaligned<NT>(src + 8 * (u * kBatchThreads + static_cast<int>(threadIdx.x)));
+#pragma unroll
+            for (int u = 0; u < kPushChunks; ++u)
+                st<NT>(reinterpret_cast<u32x4 *>(dst + a0) + u * kBatchThreads + threadIdx.x, v[u]);
+            continue;
+        }
+        int cnt[kPushChunks];
+#pragma unroll
+        for (int u = 0; u < kPushChunks; ++u) {
+            const int a_rel = 8 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            const int64_t a = a0 + a_rel;
+            cnt[u] = 0;
+            v[u] = u32x4{0u, 0u, 0u, 0u};
+            if (a >= tb.arena_elems) continue;
+            const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
+            const int64_t slot_in = a - d.shard_off;
+            const int c = valid_from(d, r, slot_in, 8);
+            if (c == 0) continue;
+            const int64_t goff = d.full_off + static_cast<int64_t>(r) * d.S + slot_in;
+            if (c == 8 || goff + 8 <= tb.full_elems) {
+                // a ragged end (c < 8) keeps the wide load: the extra lanes belong to the next
+                // piece and are dropped
+                cnt[u] = c;
+                v[u] = ld_u128_unaligned<NT>(grad + goff);
+            } else {  // the last elements of the gradient buffer
+                for (int e = 0; e < c; ++e) st_u16(dst + a + e, ld_u16(grad + goff + e));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kPushChunks; ++u) {
+            const int64_t a = a0 + 8 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
+            if (cnt[u] == 8) {
+                st<NT>(reinterpret_cast<u32x4 *>(dst + a), v[u]);
+            } else if (cnt[u] > 0) {
+                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int e = 0; e < 7; ++e)
+                    if (e < cnt[u]) st_u16(dst + a + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
+            }
         }
     }
 }

@@ -267,7 +267,8 @@ int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0
 {
     const RankPtrs rp = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
+    const int64_t chunks = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
+    const dim3 grid(batched_grid_x((chunks + kPushChunks - 1) / kPushChunks), static_cast<unsigned>(nr));
     ODC_DISPATCH_NT(tuning().nontemporal != 0,
                     (k_stage_push_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,

@@ -389,8 +389,9 @@ int main(int argc, char **argv)
                                    k_stage_push_flat<NT_>(rs, g, flags, S, N, slot, R, r0, worker);
                                }));
                     } else {
-                        const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
-                const unsigned groups = static_cast<unsigned>(nr);
+                        const int64_t chunks = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                        const int64_t tiles = (chunks + kPushChunks - 1) / kPushChunks;
+                        const unsigned groups = static_cast<unsigned>(nr);
                         EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
                                    k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, worker);
                                }));

@@ -229,7 +229,7 @@ def test_emulated_fused_accumulate(oracle, emu, tmp_path, numel, R, count, cap):
 
 @pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([4099], 8), ([1], 64),
                                      ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5),
-                                     ([5] * 66, 66)])
+                                     ([5] * 66, 66), ([40_000, 9, 20_001, 3], 2)])
 @pytest.mark.parametrize("nt,cap", [(1, 0), (0, 2)])
 def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
     """Pushes into per-client slots, drains in ascending client order, refusal of a push into
