@@ -173,26 +173,35 @@ int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const vo
  *   staging_shards [R] host array of device pointers: owner r's buffer, bf16, R slots of
  *                  odc_stage_slot_elems() elements (client w's slot starts at w * slot and
  *                  mirrors the rank arena); 16-byte aligned
- *   flags          device int32[odc_stage_flag_count()] = R*R flags (owner-major: flag of owner r,
- *                  client w at r*R + w; 0 empty, 1 full) + 1 counter of refused pushes
+ *   flags          device int32[odc_stage_flag_count()] = R*R slot states (owner-major: owner r,
+ *                  client w at r*R + w; 0 empty, 1 full, 2 being written) + 1 counter of refused pushes
  *   snapshot       device int32[odc_stage_snapshot_count()], scratch owned by the caller; a
  *                  drain writes and reads it, so two drains that overlap must not share one
  *
  * odc_stage_init   zeroes flags (a small fill kernel on `stream`).
- * odc_stage_push   copies slice r of grad_full (full layout) into slot `worker` of owner r, for
- *                  every owner whose flag (r, worker) is 0, then raises those flags.  An owner
- *                  whose slot is still full is skipped and counted in flags[R*R]: a client has
- *                  one buffer per owner, so it must not push again before the owner has drained.
+ * odc_stage_push   decides ONCE per owner, before any byte is copied, whether the owner takes the
+ *                  push: slot (r, worker) empty -> being written (an atomic compare-and-swap by
+ *                  one thread).  Slice r of grad_full (full layout) is then copied into the
+ *                  slots so claimed, and those become full.  An owner whose slot is not empty
+ *                  refuses the whole push and is counted in flags[R*R]: a client has one buffer
+ *                  per owner, so it must not push again before the owner has drained.
  *                  4 bytes per valid element.
- * odc_stage_drain  takes one snapshot of the flags; every owner with full slots reads and
- *                  writes its accumulator once and adds the staged slices in ascending client
- *                  order, acc = (((acc + s_w1) + s_w2) + ...), one binary32 add each -- the
- *                  same bits as single ordered contributions in that order; then lowers the
- *                  flags of the snapshot.  Owners with nothing staged are not touched.
+ * odc_stage_drain  takes one snapshot of the slots that are full (never one that is being
+ *                  written); every owner with full slots reads and writes its accumulator once
+ *                  and adds the staged slices in ascending client order,
+ *                  acc = (((acc + s_w1) + s_w2) + ...), one binary32 add each -- the same bits as
+ *                  single ordered contributions in that order; then empties exactly the slots
+ *                  of the snapshot.  Owners with nothing staged are not touched.
  *                  (2k + 8) bytes per valid element for k staged slices.
  * All three enqueue on `stream` and return.  Pushes and drains on one stream are ordered by
- * it; a push running concurrently with a drain on another stream is either wholly inside
- * that drain's snapshot or left for the next drain.  The ordered-mode history of
+ * it.  A push may run concurrently with a drain on another stream, however their kernels
+ * interleave: per owner the push is either refused as a whole (its slot was not empty when it
+ * was claimed) or taken as a whole and added by exactly one drain -- the one running, if its
+ * snapshot came after the push had finished, else the next.  Every flag access is a
+ * device-scope atomic with acquire/release ordering.  What the caller must serialise: the
+ * pushes of one client (one stream per client will do), and the drains of one staging set.
+ * If a push returns ODC_ERR_HIP some of its slots may be left in the "being written" state:
+ * call odc_stage_init again before reusing the staging set.  The ordered-mode history of
  * odc_scatter_accumulate is not involved: the order is the drain order.
  */
 int64_t odc_stage_slot_elems(const odc_layout_t *layout);

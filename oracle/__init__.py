@@ -359,12 +359,17 @@ def retrieve_batched(acc_arenas, out_arenas, numel, shard_off, scale: float = 1.
 class Staging:
     """Server-side staging of Appendix B, as plain bookkeeping around `accumulate`.
 
-    Every owner has one receive slot per client.  push(g, w): for every owner whose slot for
-    client w is empty, keep slice r of g there and mark it full; an owner whose slot is still
-    full refuses (counted) -- a client has one buffer per owner, and its requests are
-    serialised.  drain(acc): every owner adds its full slots to its accumulator in ascending
-    client order, one contribution after the other, and empties them.
+    Every owner has one receive slot per client, which is empty, being written, or full.
+    A push by client w is decided once per owner, when it begins: an owner whose slot for w
+    is empty keeps slice r of g there (the slot is being written until the push ends, then
+    full); an owner whose slot is not empty refuses (counted) -- a client has one buffer per
+    owner, and its requests are serialised.  A drain first notes which slots are full, adds
+    those to the accumulators in ascending client order, one contribution after the other,
+    and then empties exactly those.  push() and drain() are the undivided forms; the phase
+    methods let a test interleave a push with a drain the way two streams can.
     """
+
+    EMPTY, WRITING, FULL = 0, 2, 1
 
     def __init__(self, numel, R: int, shard_off=None, full_off=None):
         self.numel = [int(n) for n in numel]
@@ -372,32 +377,57 @@ class Staging:
         self.shard_off = list(shard_off) if shard_off is not None else [0] * len(self.numel)
         self.full_off = list(full_off) if full_off is not None else [0] * len(self.numel)
         self.slot = {}
-        self.full = [[False] * R for _ in range(R)]
+        self.state = [[self.EMPTY] * R for _ in range(R)]
         self.refused = 0
+        self.noted = []
 
-    def push(self, g_full: np.ndarray, worker: int) -> None:
+    @property
+    def full(self):
+        return [[s == self.FULL for s in row] for row in self.state]
+
+    # -- push, in two phases
+    def begin_push(self, g_full: np.ndarray, worker: int) -> None:
         for r in range(self.R):
-            if self.full[r][worker]:
+            if self.state[r][worker] != self.EMPTY:
                 self.refused += 1
             else:
                 self.slot[(r, worker)] = g_full.copy()
-                self.full[r][worker] = True
+                self.state[r][worker] = self.WRITING
+
+    def end_push(self, worker: int) -> None:
+        for r in range(self.R):
+            if self.state[r][worker] == self.WRITING:
+                self.state[r][worker] = self.FULL
+
+    def push(self, g_full: np.ndarray, worker: int) -> None:
+        self.begin_push(g_full, worker)
+        self.end_push(worker)
+
+    # -- drain, in three phases
+    def begin_drain(self) -> None:
+        self.noted = [(r, w) for r in range(self.R) for w in range(self.R) if self.state[r][w] == self.FULL]
+
+    def add_noted(self, acc_arenas) -> int:
+        for (r, w) in self.noted:
+            g = self.slot[(r, w)]
+            for t, n in enumerate(self.numel):
+                S = shard_elems(n, self.R)
+                lo, hi = r * S, min((r + 1) * S, n)
+                if hi <= lo:
+                    continue
+                views = [a[self.shard_off[t]:self.shard_off[t] + S] for a in acc_arenas]
+                accumulate(np.ascontiguousarray(g[self.full_off[t]:self.full_off[t] + n]), views, n,
+                           ranges=[(lo, hi)])
+        return len(self.noted)
+
+    def end_drain(self) -> None:
+        for (r, w) in self.noted:
+            del self.slot[(r, w)]
+            self.state[r][w] = self.EMPTY
+        self.noted = []
 
     def drain(self, acc_arenas) -> int:
-        done = 0
-        for r in range(self.R):
-            for w in range(self.R):
-                if not self.full[r][w]:
-                    continue
-                g = self.slot.pop((r, w))
-                for t, n in enumerate(self.numel):
-                    S = shard_elems(n, self.R)
-                    lo, hi = r * S, min((r + 1) * S, n)
-                    if hi <= lo:
-                        continue
-                    views = [a[self.shard_off[t]:self.shard_off[t] + S] for a in acc_arenas]
-                    accumulate(np.ascontiguousarray(g[self.full_off[t]:self.full_off[t] + n]), views, n,
-                               ranges=[(lo, hi)])
-                self.full[r][w] = False
-                done += 1
+        self.begin_drain()
+        done = self.add_noted(acc_arenas)
+        self.end_drain()
         return done

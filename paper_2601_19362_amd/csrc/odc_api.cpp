@@ -342,9 +342,11 @@ int odc_stage_push(const odc_layout_t *L, const void *grad_full, void *const *st
     if (rc != ODC_OK) return rc;
     const odc::HostLayout &H = L->host;
     const int64_t slot = stage_slot(L);
+    // claim (one decision per owner), copy into the claimed slots, raise them
+    int e = odc::launch_stage_claim(flags, H.R, worker, stream);
+    if (e != 0) return hip_fail(static_cast<hipError_t>(e));
     for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
         const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
-        int e;
         if (H.T == 1)
             e = odc::launch_stage_push_flat(staging_shards + r0, r0, nr, grad_full, flags, H.desc[0].S,
                                             H.desc[0].numel, slot, H.R, worker, stream);
@@ -353,7 +355,7 @@ int odc_stage_push(const odc_layout_t *L, const void *grad_full, void *const *st
                                                worker, stream);
         if (e != 0) return hip_fail(static_cast<hipError_t>(e));
     }
-    const int e = odc::launch_stage_raise(flags, H.R, worker, stream);
+    e = odc::launch_stage_raise(flags, H.R, worker, stream);
     return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
 }
 

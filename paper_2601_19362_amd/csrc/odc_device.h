@@ -1140,8 +1140,42 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
 //
 // Layout: owner r's staging buffer holds R slots of `slot` elements (the rank arena length
 // rounded up to 8, so every slot starts 16-byte aligned); client w's slot starts at w * slot
-// and mirrors the rank arena element for element.  flags[r * R + w] is 0 (empty) or 1 (full);
-// flags[R * R] counts refused pushes (a slot that is still full is never overwritten).
+// and mirrors the rank arena element for element.  flags[r * R + w] is the state of that slot;
+// flags[R * R] counts refused pushes (a slot that is not empty is never overwritten).
+//
+// Slot protocol.  A push and a drain may run at the same time on different streams, so the
+// fate of a push is decided ONCE per (owner, client), by one thread, before any byte is copied:
+//   claim   (one thread per owner)  compare-and-swap empty -> writing; a slot that is not empty
+//           refuses the push for that owner (counted)
+//   copy    every workgroup copies for an owner only if its slot is in state writing; nothing
+//           but this push's own raise ever leaves that state, so all workgroups agree
+//   raise   writing -> full
+//   drain   its snapshot lists the slots that are full (never one that is being written), the
+//           accumulate kernel adds exactly those, and the clear lowers exactly those to empty.
+// A push that meets a full slot is therefore refused as a whole for that owner, however a
+// concurrent drain interleaves with its kernels, and a slot is never added twice or half-old.
+// All flag accesses are device-scope atomics (acquire loads, release stores): the slot data
+// written before a raise are visible to the drain that sees the flag, and the drain's reads
+// are complete before a claim can see the slot empty again.  What the protocol assumes of the
+// caller: the pushes of one client are serialised (Appendix B), and so are the drains.
+constexpr int32_t kSlotEmpty = 0, kSlotFull = 1, kSlotWriting = 2;
+
+__device__ __forceinline__ int32_t flag_load(const int32_t *f)
+{
+    return __scoped_atomic_load_n(f, __ATOMIC_ACQUIRE, __MEMORY_SCOPE_DEVICE);
+}
+
+__device__ __forceinline__ void flag_store(int32_t *f, int32_t v)
+{
+    __scoped_atomic_store_n(f, v, __ATOMIC_RELEASE, __MEMORY_SCOPE_DEVICE);
+}
+
+// true if *f was `from` and is now `to`
+__device__ __forceinline__ bool flag_swap(int32_t *f, int32_t from, int32_t to)
+{
+    return __scoped_atomic_compare_exchange_n(f, &from, to, false, __ATOMIC_ACQ_REL, __ATOMIC_ACQUIRE,
+                                              __MEMORY_SCOPE_DEVICE);
+}
 
 // Copy `valid` bf16 elements from an unaligned source to a 16-byte-aligned destination.
 template <int TPB, bool NT>
@@ -1171,7 +1205,7 @@ __global__ __launch_bounds__(64) void k_stage_push_flat(RankPtrs staging, const 
     int64_t valid = N - base;
     if (valid > S) valid = S;
     if (valid <= 0) return;
-    if (flags[static_cast<int64_t>(r) * R + worker] != 0) return;  // slot still full: refuse
+    if (flag_load(flags + static_cast<int64_t>(r) * R + worker) != kSlotWriting) return;  // not claimed: refused
     uint16_t *dst = static_cast<uint16_t *>(staging.p[blockIdx.y]) + static_cast<int64_t>(worker) * slot;
     copy_to_aligned<64, NT>(grad + base, dst, valid);
 }
@@ -1194,10 +1228,10 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
     const int r = r0 + rl;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();
-        const int32_t taken = flags[static_cast<int64_t>(r) * R + worker];  // uniform per workgroup
+        const bool claimed = flag_load(flags + static_cast<int64_t>(r) * R + worker) == kSlotWriting;  // uniform
         int t_lo, n;
         stage_tile<kPushChunks>(tb, tile, nchunks, lds, t_lo, n);
-        if (taken != 0) continue;
+        if (!claimed) continue;  // this owner refused the push
         uint16_t *dst = static_cast<uint16_t *>(staging.p[rl]) + static_cast<int64_t>(worker) * slot;
         const int64_t a0 = tile * kTile;
         u32x4 v[kPushChunks];
@@ -1249,14 +1283,20 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
     }
 }
 
-// flags[r * R + worker] = 1 for the owners whose slot was empty; a refused push is counted.
-__global__ __launch_bounds__(64) void k_stage_raise(int32_t *flags, int R, int worker)
+// Claim: one thread per owner decides whether the owner takes this push (see the slot protocol).
+__global__ __launch_bounds__(64) void k_stage_claim(int32_t *flags, int R, int worker)
 {
     for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
-        ODC_GLOBAL int32_t *f = (ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R + worker);
-        if (*f == 0) *f = 1;
-        else atomicAdd(flags + static_cast<int64_t>(R) * R, 1);
+        if (!flag_swap(flags + static_cast<int64_t>(r) * R + worker, kSlotEmpty, kSlotWriting))
+            atomicAdd(flags + static_cast<int64_t>(R) * R, 1);
     }
+}
+
+// Raise: the slots this push claimed (and has filled by now) become full.
+__global__ __launch_bounds__(64) void k_stage_raise(int32_t *flags, int R, int worker)
+{
+    for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64)
+        (void)flag_swap(flags + static_cast<int64_t>(r) * R + worker, kSlotWriting, kSlotFull);
 }
 
 // One thread per owner.  Snapshot: the owner's full slots, ascending, are written as a list
@@ -1267,10 +1307,10 @@ __global__ __launch_bounds__(64) void k_stage_snapshot(const int32_t *flags, int
 {
     for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
         ODC_GLOBAL int32_t *list = (ODC_GLOBAL int32_t *)(snapshot + static_cast<int64_t>(r) * (R + 1));
-        const ODC_GLOBAL int32_t *row = (const ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R);
+        const int32_t *row = flags + static_cast<int64_t>(r) * R;
         int n = 0;
         for (int w = 0; w < R; ++w)
-            if (row[w] != 0) list[1 + n++] = w;
+            if (flag_load(row + w) == kSlotFull) list[1 + n++] = w;
         list[0] = n;
     }
 }
@@ -1279,9 +1319,9 @@ __global__ __launch_bounds__(64) void k_stage_clear(int32_t *flags, const int32_
 {
     for (int r = blockIdx.x * 64 + threadIdx.x; r < R; r += gridDim.x * 64) {
         const ODC_GLOBAL int32_t *list = (const ODC_GLOBAL int32_t *)(snapshot + static_cast<int64_t>(r) * (R + 1));
-        ODC_GLOBAL int32_t *row = (ODC_GLOBAL int32_t *)(flags + static_cast<int64_t>(r) * R);
+        int32_t *row = flags + static_cast<int64_t>(r) * R;
         const int n = list[0];
-        for (int k = 0; k < n; ++k) row[list[1 + k]] = 0;
+        for (int k = 0; k < n; ++k) flag_store(row + list[1 + k], kSlotEmpty);
     }
 }
 

@@ -137,6 +137,7 @@ int launch_stage_push_flat(void *const *staging, int r0, int nr, const void *gra
                            int64_t N, int64_t slot, int R, int worker, void *stream);
 int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0, int nr, const void *grad,
                               const void *flags, int64_t slot, int R, int worker, void *stream);
+int launch_stage_claim(void *flags, int R, int worker, void *stream);
 int launch_stage_raise(void *flags, int R, int worker, void *stream);
 int launch_stage_snapshot(const void *flags, void *snapshot, int R, void *stream);
 int launch_stage_clear(void *flags, const void *snapshot, int R, void *stream);

@@ -276,6 +276,13 @@ int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0
     return finish();
 }
 
+int launch_stage_claim(void *flags, int R, int worker, void *stream)
+{
+    k_stage_claim<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t *>(flags), R,
+                                                                                   worker);
+    return finish();
+}
+
 int launch_stage_raise(void *flags, int R, int worker, void *stream)
 {
     k_stage_raise<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t *>(flags), R,

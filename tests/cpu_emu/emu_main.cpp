@@ -46,6 +46,13 @@ void write_file(const std::string &path, const T *p, size_t n)
     std::fclose(f);
 }
 
+// A scripted run can execute only part of a grid: the workgroups whose linear index is
+// congruent to part_k modulo part_n (part_n = 1: all).  Used to interleave the workgroups of
+// one kernel with kernels of another stream.
+unsigned part_k = 0, part_n = 1;
+
+bool in_part(unsigned x, unsigned y, unsigned gx) { return part_n <= 1 || (y * gx + x) % part_n == part_k; }
+
 template <typename F>
 void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
 {
@@ -54,7 +61,7 @@ void run_grid(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
     blockDim.x = tpb;
     for (unsigned y = 0; y < gy; ++y)
         for (unsigned x = 0; x < gx; ++x)
-            for (unsigned t = 0; t < tpb; ++t) {
+            for (unsigned t = 0; t < tpb && in_part(x, y, gx); ++t) {
                 blockIdx.x = x;
                 blockIdx.y = y;
                 threadIdx.x = t;
@@ -78,6 +85,7 @@ void run_grid_threaded(unsigned tpb, unsigned gx, unsigned gy, F &&kernel)
         pool.emplace_back([&, t] {
             for (unsigned y = 0; y < gy; ++y)
                 for (unsigned x = 0; x < gx; ++x) {
+                    if (!in_part(x, y, gx)) continue;
                     blockIdx.x = x;
                     blockIdx.y = y;
                     threadIdx.x = t;
@@ -350,7 +358,7 @@ int main(int argc, char **argv)
     }
 
     if (op == "stage") {
-        // script: comma-separated steps; "pW" = push by worker W (k-th push reads grad<k>.u16), "d" = drain
+        // script: comma-separated steps (see below); the k-th push started reads grad<k>.u16
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;
         const int64_t slot = (H.arena_elems + kAlignElems - 1) / kAlignElems * kAlignElems;
@@ -368,61 +376,95 @@ int main(int argc, char **argv)
         std::memset(flags, 0x55, nflags * 4);
         run_grid(256, grid_x_for(static_cast<int64_t>(nflags), 256, 1024), 1, [&] { k_stage_zero(flags, static_cast<int64_t>(nflags)); });
         int pushes = 0;
+        std::vector<uint16_t *> open_grad(static_cast<size_t>(R), nullptr);  // gradient of each client's push in flight
+        auto push_claim = [&](int worker) {
+            std::vector<uint16_t> gi = read_file<uint16_t>(dir + "/grad" + std::to_string(pushes++) + ".u16");
+            if (gi.size() != full_n) std::exit(4);
+            std::free(open_grad[worker]);
+            open_grad[worker] = static_cast<uint16_t *>(std::malloc(full_n * 2));
+            std::memcpy(open_grad[worker], gi.data(), full_n * 2);
+            run_grid(64, (R + 63) / 64, 1, [&] { k_stage_claim(flags, R, worker); });
+        };
+        auto push_copy = [&](int worker) {
+            const uint16_t *g = open_grad[worker];
+            if (!g) std::exit(5);
+            for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+                const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+                RankPtrs rs{};
+                for (int k = 0; k < nr; ++k) rs.p[k] = stages[r0 + k];
+                if (flat) {
+                    EMU_NT(nt, run_grid(64, grid_x_for((S >> 3) + 1, 64, cap), nr, [&] {
+                               k_stage_push_flat<NT_>(rs, g, flags, S, N, slot, R, r0, worker);
+                           }));
+                } else {
+                    const int64_t chunks = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                    const int64_t tiles = (chunks + kPushChunks - 1) / kPushChunks;
+                    const unsigned groups = static_cast<unsigned>(nr);
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
+                               k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, worker);
+                           }));
+                }
+            }
+        };
+        auto push_raise = [&](int worker) { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_raise(flags, R, worker); }); };
+        auto drain_snapshot = [&] { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_snapshot(flags, snap, R); }); };
+        auto drain_add = [&] {
+            for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+                const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+                RankPtrs ra{}, rs{};
+                for (int k = 0; k < nr; ++k) {
+                    ra.p[k] = accs[r0 + k];
+                    rs.p[k] = stages[r0 + k];
+                }
+                if (flat) {
+                    EMU_NT(nt, run_grid(64, grid_x_for((S >> 2) + 1, 64, cap), nr, [&] {
+                               k_stage_drain_flat<NT_>(ra, rs, snap, S, N, slot, R, r0);
+                           }));
+                } else {
+                    const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
+                    const unsigned groups = static_cast<unsigned>(nr);
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
+                               k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0);
+                           }));
+                }
+            }
+        };
+        auto drain_clear = [&] { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_clear(flags, snap, R); }); };
+        // Steps: "pW" whole push by client W; its three kernels one by one: "cW" claim (takes the
+        // next grad<k>.u16), "xW" copy or "xW:k:n" only the copy workgroups congruent to k mod n,
+        // "rW" raise; "d" whole drain, or its kernels "s" snapshot, "a" add, "z" clear.
         size_t pos = 0;
         while (pos < script.size()) {
             size_t comma = script.find(',', pos);
             if (comma == std::string::npos) comma = script.size();
             const std::string step = script.substr(pos, comma - pos);
             pos = comma + 1;
-            if (step[0] == 'p') {
-                const int worker = std::atoi(step.c_str() + 1);
-                std::vector<uint16_t> gi = read_file<uint16_t>(dir + "/grad" + std::to_string(pushes++) + ".u16");
-                if (gi.size() != full_n) return 4;
-                uint16_t *g = static_cast<uint16_t *>(std::malloc(full_n * 2));
-                std::memcpy(g, gi.data(), full_n * 2);
-                for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
-                    const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
-                    RankPtrs rs{};
-                    for (int k = 0; k < nr; ++k) rs.p[k] = stages[r0 + k];
-                    if (flat) {
-                        EMU_NT(nt, run_grid(64, grid_x_for((S >> 3) + 1, 64, cap), nr, [&] {
-                                   k_stage_push_flat<NT_>(rs, g, flags, S, N, slot, R, r0, worker);
-                               }));
-                    } else {
-                        const int64_t chunks = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
-                        const int64_t tiles = (chunks + kPushChunks - 1) / kPushChunks;
-                        const unsigned groups = static_cast<unsigned>(nr);
-                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
-                                   k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, worker);
-                               }));
+            const int worker = step.size() > 1 ? std::atoi(step.c_str() + 1) : 0;
+            switch (step[0]) {
+                case 'p': push_claim(worker); push_copy(worker); push_raise(worker); break;
+                case 'c': push_claim(worker); break;
+                case 'x': {
+                    const size_t c1 = step.find(':');
+                    if (c1 != std::string::npos) {
+                        const size_t c2 = step.find(':', c1 + 1);
+                        if (c2 == std::string::npos) return 2;
+                        part_k = static_cast<unsigned>(std::atoi(step.c_str() + c1 + 1));
+                        part_n = static_cast<unsigned>(std::atoi(step.c_str() + c2 + 1));
                     }
+                    push_copy(worker);
+                    part_k = 0;
+                    part_n = 1;
+                    break;
                 }
-                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_raise(flags, R, worker); });
-                std::free(g);
-            } else {
-                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_snapshot(flags, snap, R); });
-                for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
-                    const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
-                    RankPtrs ra{}, rs{};
-                    for (int k = 0; k < nr; ++k) {
-                        ra.p[k] = accs[r0 + k];
-                        rs.p[k] = stages[r0 + k];
-                    }
-                    if (flat) {
-                        EMU_NT(nt, run_grid(64, grid_x_for((S >> 2) + 1, 64, cap), nr, [&] {
-                                   k_stage_drain_flat<NT_>(ra, rs, snap, S, N, slot, R, r0);
-                               }));
-                    } else {
-                        const int64_t tiles = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
-                const unsigned groups = static_cast<unsigned>(nr);
-                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
-                                   k_stage_drain_batched<NT_>(tb, ra, rs, snap, slot, R, r0);
-                               }));
-                    }
-                }
-                run_grid(64, (R + 63) / 64, 1, [&] { k_stage_clear(flags, snap, R); });
+                case 'r': push_raise(worker); break;
+                case 'd': drain_snapshot(); drain_add(); drain_clear(); break;
+                case 's': drain_snapshot(); break;
+                case 'a': drain_add(); break;
+                case 'z': drain_clear(); break;
+                default: std::fprintf(stderr, "unknown step %s\n", step.c_str()); return 2;
             }
         }
+        for (auto *g : open_grad) std::free(g);
         std::vector<float> out(arena * static_cast<size_t>(R));
         for (int r = 0; r < R; ++r) std::memcpy(out.data() + arena * r, accs[r], arena * 4);
         write_file(dir + "/acc.out", out.data(), out.size());

@@ -458,6 +458,53 @@ def test_staging_concurrent_push_and_drain_loses_nothing():
     case.close()
 
 
+def test_staging_repeated_pushes_race_drains_on_another_stream():
+    """Two clients push five times each, back to back on a stream of their own, without waiting
+    for the owners; drains run meanwhile on a third stream.  Whether an owner takes a given push
+    depends on timing -- its slot may still be full -- but each owner decides once per push: a
+    push is added exactly once in full or refused in full and counted.  Push i of client w
+    carries 4^(5w+i) * (1 + j mod 3) at flat index j (exact in bf16, every partial sum exact in
+    binary32), so an accumulator element divided by (1 + j mod 3) spells in base 4 how often
+    each push was added: every digit must be 0 or 1, the same over the whole shard of an owner,
+    and the zeros must add up to the refused counter."""
+    N, R, K, clients = 48_000_005, 8, 5, (0, 5)
+    case = DeviceCase(R, [N], with_params=False)
+    st = DeviceStaging(case)
+    case.layout.reset_accum(case.acc_ptrs)
+    pos = (torch.arange(N, device="cuda") % 3 + 1).to(torch.float32)
+    grads = {(w, i): (pos * float(4 ** (K * c + i))).to(torch.bfloat16) for c, w in enumerate(clients) for i in range(K)}
+    for g in grads.values():
+        assert torch.equal(g.to(torch.float32) / pos, torch.full_like(pos, float(g[0])))   # exact in bf16
+    torch.cuda.synchronize()
+    s_client = {w: torch.cuda.Stream() for w in clients}
+    s_drain = torch.cuda.Stream()
+    for i in range(K):
+        for w in clients:
+            case.layout.stage_push(grads[(w, i)], st.bufs, st.flags, w, stream=s_client[w])
+        case.layout.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs, stream=s_drain)
+        case.layout.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs, stream=s_drain)
+    torch.cuda.synchronize()
+    case.layout.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs)      # whatever is left
+    torch.cuda.synchronize()
+    flags = st.flags.cpu().numpy()
+    assert not flags[:R * R].any()
+    S = case.S[0]
+    taken = 0
+    pos_h = (np.arange(N) % 3 + 1).astype(np.float64)
+    for r, a in enumerate(case.acc_host()):
+        valid = max(0, min(S, N - r * S))
+        code = a[:valid].astype(np.float64) / pos_h[r * S:r * S + valid]
+        assert (code == code[0]).all(), f"owner {r}: pushes added to part of the shard only"
+        digits = [int(code[0]) // 4 ** d % 4 for d in range(K * len(clients))]
+        assert int(code[0]) == code[0] and all(d in (0, 1) for d in digits), f"owner {r}: base-4 digits {digits}"
+        taken += sum(digits)
+    refused = int(flags[R * R])
+    print(f"staging race: {taken} pushes taken, {refused} refused of {R * K * len(clients)}", flush=True)
+    assert taken + refused == R * K * len(clients)
+    case.check_guards()
+    case.close()
+
+
 def test_staging_argument_errors():
     case = DeviceCase(4, [1000], with_params=False)
     st = DeviceStaging(case)

@@ -261,6 +261,63 @@ def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
     assert flags[R * R] == model.refused and model.refused >= R     # at least the second push of worker 0
 
 
+INTERLEAVINGS = [
+    # a client pushes again while its slot is full; a drain on another stream empties the slot
+    # after the claim / between the copy workgroups / before the raise
+    "p0,c0,s,a,z,x0,r0,d",
+    "p0,c0,x0:0:2,s,a,z,x0:1:2,r0,d",
+    "p0,c0,x0,s,a,z,r0,d",
+    "p0,s,c0,a,x0,z,r0,d",
+    # a drain begins while a push is being written: left for the next drain, added once
+    "c1,s,x1,a,z,r1,d",
+    "c1,x1:1:3,s,a,x1:0:3,z,x1:2:3,r1,s,a,z",
+    # another client's push lands inside a drain
+    "p0,s,c1,x1,r1,a,z,d",
+    "p0,p1,s,a,c0,x0,r0,z,c0,x0,r0,d",
+]
+
+
+@pytest.mark.parametrize("numel,R", [([8 * 1024 * 3 + 5], 4), ([30000, 17, 2048, 2049], 5), ([5] * 66, 66)])
+@pytest.mark.parametrize("script", INTERLEAVINGS)
+def test_emulated_staging_interleavings(oracle, emu, tmp_path, numel, R, script):
+    """The kernels of a push and of a drain run in a scripted order, as two streams could run
+    them (including a drain that empties a slot between the workgroups of a push's copy kernel).
+    The phased bookkeeping model decides once per push and owner; the kernels must agree: every
+    accepted contribution is added exactly once, a refused one never, and no slot is left full
+    that the model has empty."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc, numel, so)
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    model = oracle.Staging(numel, R, so, fo)
+    k = 0
+    for step in script.split(","):
+        kind, w = step[0], int(step[1:].split(":")[0]) if len(step) > 1 else 0
+        if kind in "pc":
+            g = inputs.normal_bf16(full_n, 1e-2, seed=(19, k))
+            g.tofile(tmp_path / f"grad{k}.u16")
+            k += 1
+            model.begin_push(g, w)
+            if kind == "p":
+                model.end_push(w)
+        elif kind == "r":
+            model.end_push(w)
+        elif kind in "ds":
+            model.begin_drain()
+            model.add_noted(acc)
+            if kind == "d":
+                model.end_drain()
+        elif kind == "z":
+            model.end_drain()
+    run(emu, tmp_path, "stage", R, script=script)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+    flags = np.fromfile(tmp_path / "flags.out", dtype=np.int32)
+    assert flags[:R * R].reshape(R, R).tolist() == model.state
+    assert flags[R * R] == model.refused
+
+
 def random_layout(seed):
     """A seeded random multi-tensor layout: tensor sizes from a mixture of tiny, small, medium
     and large, a rank count from single-launch and multi-launch values; at most about 250,000

@@ -462,3 +462,65 @@ def test_staging_model_is_ordered_accumulation_by_client(oracle):
     for a, b in zip(acc, ref):
         assert np.array_equal(bits32(a), bits32(b))
     assert not any(any(row) for row in st.full)
+
+
+def test_staging_model_phases(oracle):
+    """The phased form of the staging bookkeeping, against outcomes written out by hand: the
+    fate of a push is fixed when it begins (a slot that is full or being written refuses it as a
+    whole, even if a drain empties the slot before the push ends), and a drain takes exactly
+    the slots that were full when it began."""
+    N, R = 1001, 4
+    S = -(-N // R)
+    gs = {k: inputs.normal_bf16(N, 1e-3, seed=(71, k)) for k in range(4)}
+
+    def fresh():
+        acc, ref = new_acc(S, R), new_acc(S, R)
+        oracle.reset(acc, N)
+        oracle.reset(ref, N)
+        return oracle.Staging([N], R), acc, ref
+
+    def same(acc, ref):
+        return all(np.array_equal(bits32(a), bits32(b)) for a, b in zip(acc, ref))
+
+    # a second push of one client begins while its slot is full; a drain runs before it ends
+    st, acc, ref = fresh()
+    st.push(gs[0], 0)
+    st.begin_push(gs[1], 0)
+    assert st.refused == R
+    assert st.drain(acc) == R
+    st.end_push(0)                       # ends a push that no owner took: nothing becomes full
+    assert not any(any(row) for row in st.full)
+    assert st.drain(acc) == 0
+    oracle.accumulate(gs[0], ref, N)
+    assert same(acc, ref)
+
+    # a drain that begins while a push is being written leaves it for the next drain
+    st, acc, ref = fresh()
+    st.begin_push(gs[0], 2)
+    st.begin_drain()
+    st.end_push(2)
+    assert st.add_noted(acc) == 0
+    st.end_drain()
+    assert same(acc, ref) and all(row[2] for row in st.full)
+    assert st.drain(acc) == R
+    oracle.accumulate(gs[0], ref, N)
+    assert same(acc, ref)
+
+    # a push that lands between a drain's beginning and its end is not emptied by that drain;
+    # a client whose slot the drain has noted but not yet emptied is still refused
+    st, acc, ref = fresh()
+    st.push(gs[0], 0)
+    st.begin_drain()
+    st.push(gs[1], 1)
+    st.begin_push(gs[2], 0)
+    assert st.refused == R
+    assert st.add_noted(acc) == R
+    st.end_drain()
+    st.end_push(0)
+    assert [row[:2] for row in st.full] == [[False, True]] * R
+    st.push(gs[3], 0)
+    assert st.refused == R
+    assert st.drain(acc) == 2 * R
+    for k in (0, 3, 1):                  # first drain: client 0; second: client 0 before client 1
+        oracle.accumulate(gs[k], ref, N)
+    assert same(acc, ref)
