@@ -49,6 +49,7 @@ typedef struct odc_layout odc_layout_t; /* opaque; owned by the library */
 #define ODC_ERR_HIP (-5)         /* a HIP call failed; see odc_last_hip_error() */
 #define ODC_ERR_NO_DEVICE (-6)   /* layout was built host-only, or belongs to another device */
 #define ODC_ERR_NOMEM (-7)       /* host allocation failed */
+#define ODC_ERR_TOO_LARGE (-8)   /* size beyond the fixed scratch of a no-allocation entry point */
 
 #define ODC_MAX_RANKS 4096
 
@@ -212,6 +213,23 @@ int odc_stage_push(const odc_layout_t *layout, const void *grad_full, void *cons
                    void *flags, int worker, void *stream);
 int odc_stage_drain(const odc_layout_t *layout, const void *const *staging_shards, void *flags,
                     void *snapshot, void *const *accum_shards, void *stream);
+
+/*
+ * odc_stage_drain for callers that cannot allocate and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * result as odc_stage_drain without `snapshot`: the snapshot list lives in a fixed device array
+ * inside the library (ODC_NOALLOC_MAX_RANKS * (ODC_NOALLOC_MAX_RANKS + 1) int32 = 263,168
+ * bytes, one copy per GPU the library runs on, held until the process ends).  The call
+ * allocates and frees nothing, on the host or on the device.  Layouts with more than
+ * ODC_NOALLOC_MAX_RANKS ranks are refused with ODC_ERR_TOO_LARGE, nothing enqueued.  All calls
+ * on one GPU share the one array: calls that may overlap in time (different streams, or
+ * different layouts on different streams) race on it -- serialise them, or use
+ * odc_stage_drain with a workspace each.  Nothing needs clearing between calls: every drain
+ * rewrites the part of the array it reads.
+ */
+#define ODC_NOALLOC_MAX_RANKS 256
+int odc_stage_drain_noalloc(const odc_layout_t *layout, const void *const *staging_shards, void *flags,
+                            void *const *accum_shards, void *stream);
 
 /* odc_retrieve_grads output types */
 #define ODC_OUT_F32 0

@@ -20,6 +20,8 @@ ODC_ERR_OVERFLOW = -4
 ODC_ERR_HIP = -5
 ODC_ERR_NO_DEVICE = -6
 ODC_ERR_NOMEM = -7
+ODC_ERR_TOO_LARGE = -8
+ODC_NOALLOC_MAX_RANKS = 256
 ODC_MAX_RANKS = 4096
 ODC_LAYOUT_HOST_ONLY = 1
 ODC_ORDERED = 0
@@ -34,7 +36,7 @@ EXPORTS = (
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
     "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
     "odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count", "odc_stage_init",
-    "odc_stage_push", "odc_stage_drain", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+    "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
 _i64 = ctypes.c_int64
@@ -100,6 +102,8 @@ def lib():
         L.odc_stage_push.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _vp, _int, _vp]
         L.odc_stage_drain.restype = _int
         L.odc_stage_drain.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, ctypes.POINTER(_vp), _vp]
+        L.odc_stage_drain_noalloc.restype = _int
+        L.odc_stage_drain_noalloc.argtypes = [_vp, ctypes.POINTER(_vp), _vp, ctypes.POINTER(_vp), _vp]
         L.odc_retrieve_grads.restype = _int
         L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
@@ -270,6 +274,11 @@ class Layout:
         if rc != ODC_OK:
             raise OdcError(rc, "odc_stage_drain")
 
+    def stage_drain_noalloc(self, staging_shards, flags, accum_shards, stream=None) -> None:
+        rc = stage_drain_noalloc_rc(self, staging_shards, flags, accum_shards, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_stage_drain_noalloc")
+
     def retrieve_grads(self, accum_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
                        stream=None) -> None:
         rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
@@ -313,6 +322,11 @@ def stage_push_rc(layout: Layout, grad_full, staging_shards, flags, worker: int,
 def stage_drain_rc(layout: Layout, staging_shards, flags, snapshot, accum_shards, stream=None) -> int:
     return lib().odc_stage_drain(layout.handle, _ptr_array(staging_shards, layout.R), _ptr(flags), _ptr(snapshot),
                                  _ptr_array(accum_shards, layout.R), _stream(stream))
+
+
+def stage_drain_noalloc_rc(layout: Layout, staging_shards, flags, accum_shards, stream=None) -> int:
+    return lib().odc_stage_drain_noalloc(layout.handle, _ptr_array(staging_shards, layout.R), _ptr(flags),
+                                         _ptr_array(accum_shards, layout.R), _stream(stream))
 
 
 def retrieve_grads_rc(layout: Layout, accum_shards, out_shards, scale: float = 1.0,

@@ -46,6 +46,13 @@ int upload_table(odc_layout_t *L)
 {
     hipError_t e = hipGetDevice(&L->device);
     if (e != hipSuccess) return hip_fail(e);
+    if (L->host.R <= odc::kStageScratchMaxRanks) {
+        // look the fixed scratch of odc_stage_drain_noalloc up now, so that its first call on
+        // this device does not have to (the lookup may load the code object)
+        int32_t *unused = nullptr;
+        const int se = odc::stage_scratch(L->device, &unused);
+        if (se != 0) return hip_fail(static_cast<hipError_t>(se));
+    }
     if (L->host.T == 1) return ODC_OK;  // flat kernels need no table
     const odc::HostLayout &H = L->host;
     const size_t T = static_cast<size_t>(H.T);
@@ -359,17 +366,10 @@ int odc_stage_push(const odc_layout_t *L, const void *grad_full, void *const *st
     return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
 }
 
-int odc_stage_drain(const odc_layout_t *L, const void *const *staging_shards, void *flags, void *snapshot,
-                    void *const *accum_shards, void *stream)
+// Shared by the two drain entry points; `snapshot` is the caller's workspace or the fixed scratch.
+static int stage_drain_impl(const odc_layout_t *L, const void *const *staging_shards, void *flags, void *snapshot,
+                            void *const *accum_shards, void *stream)
 {
-    int rc = check_launchable(L, staging_shards);
-    if (rc != ODC_OK) return rc;
-    rc = check_launchable(L, accum_shards);
-    if (rc != ODC_OK) return rc;
-    if (!flags || !snapshot) return ODC_ERR_INVALID_ARG;
-    if (!aligned16(flags) || !aligned16(snapshot)) return ODC_ERR_ALIGNMENT;
-    rc = check_device(L);
-    if (rc != ODC_OK) return rc;
     const odc::HostLayout &H = L->host;
     const int64_t slot = stage_slot(L);
     int e = odc::launch_stage_snapshot(flags, snapshot, H.R, stream);
@@ -386,6 +386,44 @@ int odc_stage_drain(const odc_layout_t *L, const void *const *staging_shards, vo
     }
     e = odc::launch_stage_clear(flags, snapshot, H.R, stream);
     return e == 0 ? ODC_OK : hip_fail(static_cast<hipError_t>(e));
+}
+
+static int check_drain_args(const odc_layout_t *L, const void *const *staging_shards, void *flags,
+                            void *const *accum_shards)
+{
+    int rc = check_launchable(L, staging_shards);
+    if (rc != ODC_OK) return rc;
+    rc = check_launchable(L, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (!flags) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(flags)) return ODC_ERR_ALIGNMENT;
+    return ODC_OK;
+}
+
+int odc_stage_drain(const odc_layout_t *L, const void *const *staging_shards, void *flags, void *snapshot,
+                    void *const *accum_shards, void *stream)
+{
+    int rc = check_drain_args(L, staging_shards, flags, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (!snapshot) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(snapshot)) return ODC_ERR_ALIGNMENT;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    return stage_drain_impl(L, staging_shards, flags, snapshot, accum_shards, stream);
+}
+
+int odc_stage_drain_noalloc(const odc_layout_t *L, const void *const *staging_shards, void *flags,
+                            void *const *accum_shards, void *stream)
+{
+    int rc = check_drain_args(L, staging_shards, flags, accum_shards);
+    if (rc != ODC_OK) return rc;
+    if (L->host.R > ODC_NOALLOC_MAX_RANKS) return ODC_ERR_TOO_LARGE;
+    rc = check_device(L);  // the layout's device is the current one
+    if (rc != ODC_OK) return rc;
+    int32_t *scratch = nullptr;
+    const int e = odc::stage_scratch(L->device, &scratch);
+    if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    return stage_drain_impl(L, staging_shards, flags, scratch, accum_shards, stream);
 }
 
 int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, void *const *out_shards,
@@ -447,6 +485,7 @@ const char *odc_strerror(int code)
         case ODC_ERR_HIP: return "HIP call failed (see odc_last_hip_error)";
         case ODC_ERR_NO_DEVICE: return "layout is host-only or belongs to another device";
         case ODC_ERR_NOMEM: return "host allocation failed";
+        case ODC_ERR_TOO_LARGE: return "size exceeds the fixed scratch of a no-allocation entry point";
         default: return "unknown ODC error code";
     }
 }

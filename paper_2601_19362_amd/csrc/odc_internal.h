@@ -145,6 +145,10 @@ int launch_stage_drain_flat(void *const *accs, const void *const *staging, int r
                             int64_t S, int64_t N, int64_t slot, int R, void *stream);
 int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const void *const *staging, int r0, int nr,
                                const void *snapshot, int64_t slot, int R, void *stream);
+// Device address, on the current device `device`, of the library's fixed snapshot scratch
+// (room for kStageScratchMaxRanks owners); looked up on first use per device, no allocation.
+constexpr int kStageScratchMaxRanks = 256;
+int stage_scratch(int device, int32_t **out);
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream);
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,

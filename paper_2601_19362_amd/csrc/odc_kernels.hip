@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "odc_device.h"
 #include "odc_internal.h"
@@ -365,6 +366,35 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
                         (k_retrieve_batched<RG_, NT_, false><<<grid, kBatchThreads, 0, s>>>(tb, ra, ro, r0, nr, scale)));
     }
     return finish();
+}
+
+// ------------------------------------------------------------------ fixed scratch, no allocation
+// Snapshot list of odc_stage_drain_noalloc: lives in the code object, one copy per GPU, so the
+// entry point needs no workspace from the caller and never allocates.  The array's name is
+// only a host-side handle; its device address is looked up once per device and kept.
+namespace {
+constexpr int kScratchDevices = 64;
+static __device__ __align__(256) int32_t scratch[kStageScratchMaxRanks * (kStageScratchMaxRanks + 1)];
+std::mutex scratch_mu;
+int32_t *scratch_ptr[kScratchDevices] = {};
+}  // namespace
+
+int stage_scratch(int device, int32_t **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kScratchDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[device]) {
+        // `device` is the current device (the caller has checked): the lookup returns the
+        // address of this device's copy of the array
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return static_cast<int>(e);
+        if (!p) return static_cast<int>(hipErrorInvalidSymbol);
+        scratch_ptr[device] = static_cast<int32_t *>(p);
+    }
+    *out = scratch_ptr[device];
+    return 0;
 }
 
 int launch_probe_copy(void *dst, const void *src, int64_t bytes, void *stream)
