@@ -13,7 +13,8 @@ sequence of operations unchanged.
 Paper passages followed: Section 3 (gather and scatter-accumulate as the point-to-point
 decomposition of all-gather and reduce-scatter), Section 3.1 (even partition),
 Section 2.1 (accumulated gradient = sum of the contributions, w_m = 1), Appendix B
-(owner accumulates on receipt), Section 3.2 (accumulators are per minibatch).
+(owner accumulates on receipt), Section 3.2 (accumulators are per minibatch), Section 6.1
+(hybrid sharding: the groups' gradient shards are summed at the minibatch end).
 """
 from __future__ import annotations
 
@@ -86,6 +87,10 @@ def _load():
             lib.odc_oracle_accumulate_weighted_batched.argtypes = [_vp, _vpp, _i64, _vp, _vp, _vp, _i64, _f32]
             lib.odc_oracle_retrieve_batched.restype = ctypes.c_int
             lib.odc_oracle_retrieve_batched.argtypes = [_vpp, _vpp, _i64, _vp, _vp, _i64, _f32, ctypes.c_int]
+            lib.odc_oracle_reduce_groups.restype = None
+            lib.odc_oracle_reduce_groups.argtypes = [_vpp, _i64, _vpp, _i64, _i64, _i64, _i64]
+            lib.odc_oracle_reduce_groups_batched.restype = ctypes.c_int
+            lib.odc_oracle_reduce_groups_batched.argtypes = [_vpp, _i64, _vpp, _i64, _vp, _vp, _i64]
             _lib = lib
     return _lib
 
@@ -240,6 +245,40 @@ def retrieve(acc, out, N: int, scale: float = 1.0, nthreads: int = 1, ranges=Non
     sc = float(np.float32(scale))
     fn = lib.odc_oracle_retrieve_bf16 if to_bf16 else lib.odc_oracle_retrieve_f32
     _run_ranges(lambda a, b: fn(pa, po, N, R, sc, a, b), N, nthreads, ranges)
+
+
+def reduce_groups(group_acc, out, N: int, nthreads: int = 1, ranges=None) -> None:
+    """Hybrid sharding (Section 6.1): out_r = ((a_0r + a_1r) + ...) over the K groups' shard r, in
+    ascending group order, one binary32 add each.  group_acc[k][r] is group k's accumulator
+    shard of owner r; out[r] may be group_acc[0][r]."""
+    K, R = len(group_acc), len(out)
+    S = shard_elems(N, R)
+    flat = []
+    for k, grp in enumerate(group_acc):
+        if len(grp) != R:
+            raise ValueError("every group needs R shards")
+        for r, a in enumerate(grp):
+            _check(a, np.float32, S, f"group_acc[{k}][{r}]")
+            flat.append(a)
+    for r, a in enumerate(out):
+        _check(a, np.float32, S, f"out[{r}]")
+    lib = _load()
+    pg, po = _ptr_array(flat), _ptr_array(out)
+    _run_ranges(lambda a, b: lib.odc_oracle_reduce_groups(pg, K, po, N, R, a, b), N, nthreads, ranges)
+
+
+def reduce_groups_batched(group_arenas, out_arenas, numel, shard_off) -> None:
+    K, R = len(group_arenas), len(out_arenas)
+    numel, shard_off = _i64_array(numel), _i64_array(shard_off)
+    flat = []
+    for grp in group_arenas:
+        _bounds_batched(grp, np.float32, numel, shard_off, R, "group_arenas")
+        flat.extend(grp)
+    _bounds_batched(out_arenas, np.float32, numel, shard_off, R, "out_arenas")
+    rc = _load().odc_oracle_reduce_groups_batched(_ptr_array(flat), K, _ptr_array(out_arenas), numel.shape[0],
+                                                  numel.ctypes.data, shard_off.ctypes.data, R)
+    if rc != 0:
+        raise MemoryError("oracle scratch allocation failed")
 
 
 def scatter_accumulate_ordered(grads, acc, N: int, nthreads: int = 1) -> int:

@@ -150,8 +150,8 @@ void odc_oracle_accumulate(const uint16_t *g, float *const *acc, int64_t N, int6
 
 /*
  * Weighted contribution (Section 2.1: the accumulated gradient is the sum over microbatches
- * of w_m * g^(m), with w_m = 1 for a plain sum "or proportional weighting when averaging by
- * tokens or samples").  The paper does not say how the product is rounded; the reading taken
+ * of w_m * g^(m), where w_m is 1 for a plain sum and a token- or sample-proportional weight
+ * for an average).  The paper does not say how the product is rounded; the reading taken
  * is one fused multiply-add in binary32 per element,
  *   acc_r[i] = fma32(w, widen(g[r*S + i]), acc_r[i]),
  * i.e. a single rounding of the exact value w*g + acc.  fmaf() is the correctly rounded C99
@@ -181,9 +181,10 @@ static uint16_t narrow_to_bf16(float f)
 }
 
 /*
- * Retrieval at the minibatch end (Section 3.2: integrating ODC needs only "retrieving
- * accumulated gradients at the minibatch end"; after it each owner holds what reduce-scatter
- * would have left on the device, Section 2.2).  Owner r's valid accumulator elements are
+ * Retrieval at the minibatch end (Section 3.2: besides swapping the collectives for the two
+ * primitives, an integration only has to read the accumulated gradients back once per
+ * minibatch; after it each owner holds what reduce-scatter would have left on the device,
+ * Section 2.2).  Owner r's valid accumulator elements are
  * read, multiplied by `scale` (1 for a plain sum, 1/tokens or 1/samples for an average) with
  * one binary32 multiplication, and written out either as binary32 or, rounded once more to
  * nearest-even, as bf16.  The accumulators are not changed; padding slots of the outputs are
@@ -213,6 +214,34 @@ void odc_oracle_retrieve_bf16(const float *const *acc, uint16_t *const *out, int
         for (int64_t i = i0; i < i1; ++i) {
             float v = scale * acc[r][i];
             out[r][i] = narrow_to_bf16(v);
+        }
+    }
+}
+
+/*
+ * Hybrid sharding (Section 6.1; Appendix E): parameters and gradients are sharded inside a
+ * group of R devices only (a node), so each of the K groups ends a minibatch holding its own
+ * accumulated gradient shards, and shard r of the minibatch gradient is the sum over the K
+ * groups of their shard r (the step that crosses nodes once per minibatch, in place of the
+ * per-layer cross-node traffic of full sharding).  The paper does not fix the order of that
+ * sum; the reading taken is ascending group order, one binary32 addition per further group:
+ *   out_r[i] = (((a_{0,r}[i] + a_{1,r}[i]) + a_{2,r}[i]) + ... + a_{K-1,r}[i])   for valid i.
+ * group_acc is group-major: group k's shard of owner r is group_acc[k*R + r].  out_r may be
+ * group 0's shard r (the sum then replaces it).  Padding slots are never read or written.
+ */
+void odc_oracle_reduce_groups(const float *const *group_acc, int64_t K, float *const *out,
+                              int64_t N, int64_t R, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i) {
+            float s = group_acc[r][i];
+            for (int64_t k = 1; k < K; ++k)
+                s = s + group_acc[k * R + r][i];
+            out[r][i] = s;
         }
     }
 }
@@ -305,6 +334,26 @@ int odc_oracle_retrieve_batched(const float *const *acc_arenas, void *const *out
             odc_oracle_retrieve_f32(ac, (float *const *)ou, numel[t], R, scale, 0, numel[t]);
     }
     free(ac);
+    free(ou);
+    return 0;
+}
+
+int odc_oracle_reduce_groups_batched(const float *const *group_arenas, int64_t K, float *const *out_arenas,
+                                     int64_t T, const int64_t *numel, const int64_t *shard_off, int64_t R)
+{
+    const float **ga = (const float **)malloc((size_t)(K * R) * sizeof *ga);
+    float **ou = (float **)malloc((size_t)R * sizeof *ou);
+    if (!ga || !ou) {
+        free(ga);
+        free(ou);
+        return -1;
+    }
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t q = 0; q < K * R; ++q) ga[q] = group_arenas[q] + shard_off[t];
+        for (int64_t r = 0; r < R; ++r) ou[r] = out_arenas[r] + shard_off[t];
+        odc_oracle_reduce_groups(ga, K, ou, numel[t], R, 0, numel[t]);
+    }
+    free(ga);
     free(ou);
     return 0;
 }
