@@ -251,6 +251,42 @@ int odc_retrieve_grads(const odc_layout_t *layout, const void *const *accum_shar
                        void *const *out_shards, float scale, int out_dtype, void *stream);
 
 /*
+ * Hybrid sharding (Section 6.1, Appendix E).  Parameters and gradients are sharded only inside
+ * a group of R devices (a node); the world is `groups` such groups, world rank w belongs to
+ * group w / R with local rank w % R.  Every group holds a full copy of the parameter shards
+ * and its own set of accumulator shards, so gather and scatter-accumulate never leave the
+ * group; once per minibatch the groups' gradient shards are summed (the one step that crosses
+ * nodes), and the optimizer states stay partitioned over all groups * R devices: device
+ * (group k, owner r) keeps piece k of shard r, slots [k*P, (k+1)*P) with P = ceil(S_t / groups).
+ *
+ *   group-major arrays: [groups * R] host arrays of device pointers, entry k*R + r = group k's
+ *   buffer of owner r (same sizes and alignment as in the plain calls).
+ *
+ * odc_hybrid_group_of            w / R, or -1 if w is outside [0, groups * R) or groups is bad.
+ * odc_gather_hybrid              odc_gather from the shards of the worker's own group.
+ * odc_scatter_accumulate_hybrid  odc_scatter_accumulate into the accumulators of the worker's own
+ *                                group with its local rank; ordered mode and its history are per
+ *                                group (ascending (local rank, microbatch) within a group).
+ * odc_reduce_groups              minibatch end:
+ *                                  out_shards[r][i] = ((a_0r[i] + a_1r[i]) + a_2r[i]) + ...  i valid
+ *                                ascending group order, one binary32 add per further group (the
+ *                                paper leaves the order open; this is the reading taken).
+ *                                out_shards [R] may be group 0's accumulators (the sum replaces
+ *                                them) but no other group's (ODC_ERR_INVALID_ARG).  Follow with
+ *                                odc_retrieve_grads on out_shards.  Enqueues one kernel per 16
+ *                                owners and per 8 groups.  (groups + 1) * 4 bytes per valid element.
+ */
+#define ODC_MAX_GROUPS 1024
+int odc_hybrid_group_of(const odc_layout_t *layout, int groups, int world_worker);
+int odc_gather_hybrid(const odc_layout_t *layout, int groups, const void *const *group_param_shards,
+                      int world_worker, void *full_out, void *stream);
+int odc_scatter_accumulate_hybrid(const odc_layout_t *layout, int groups, const void *grad_full,
+                                  void *const *group_accum_shards, int world_worker, int microbatch,
+                                  int flags, void *stream);
+int odc_reduce_groups(const odc_layout_t *layout, int groups, const void *const *group_accum_shards,
+                      void *const *out_shards, void *stream);
+
+/*
  * Start of a minibatch (Section 3.2: accumulated gradients are retrieved at the minibatch
  * end, so accumulators are cleared before the next one): every valid accumulator element
  * becomes +0.0f.  Also clears the ordered-mode history of this accumulator set.

@@ -22,6 +22,7 @@ ODC_ERR_NO_DEVICE = -6
 ODC_ERR_NOMEM = -7
 ODC_ERR_TOO_LARGE = -8
 ODC_NOALLOC_MAX_RANKS = 256
+ODC_MAX_GROUPS = 1024
 ODC_MAX_RANKS = 4096
 ODC_LAYOUT_HOST_ONLY = 1
 ODC_ORDERED = 0
@@ -36,7 +37,8 @@ EXPORTS = (
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
     "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
     "odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count", "odc_stage_init",
-    "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
+    "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_hybrid_group_of",
+    "odc_gather_hybrid", "odc_scatter_accumulate_hybrid", "odc_reduce_groups", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
 _i64 = ctypes.c_int64
@@ -104,6 +106,14 @@ def lib():
         L.odc_stage_drain.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, ctypes.POINTER(_vp), _vp]
         L.odc_stage_drain_noalloc.restype = _int
         L.odc_stage_drain_noalloc.argtypes = [_vp, ctypes.POINTER(_vp), _vp, ctypes.POINTER(_vp), _vp]
+        L.odc_hybrid_group_of.restype = _int
+        L.odc_hybrid_group_of.argtypes = [_vp, _int, _int]
+        L.odc_gather_hybrid.restype = _int
+        L.odc_gather_hybrid.argtypes = [_vp, _int, ctypes.POINTER(_vp), _int, _vp, _vp]
+        L.odc_scatter_accumulate_hybrid.restype = _int
+        L.odc_scatter_accumulate_hybrid.argtypes = [_vp, _int, _vp, ctypes.POINTER(_vp), _int, _int, _int, _vp]
+        L.odc_reduce_groups.restype = _int
+        L.odc_reduce_groups.argtypes = [_vp, _int, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]
         L.odc_retrieve_grads.restype = _int
         L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
@@ -279,6 +289,28 @@ class Layout:
         if rc != ODC_OK:
             raise OdcError(rc, "odc_stage_drain_noalloc")
 
+    # -- hybrid sharding: group-major lists of groups * R buffers
+    def hybrid_group_of(self, groups: int, world_worker: int) -> int:
+        return lib().odc_hybrid_group_of(self._h, int(groups), int(world_worker))
+
+    def gather_hybrid(self, groups: int, group_param_shards, world_worker: int, full_out, stream=None) -> None:
+        rc = lib().odc_gather_hybrid(self._h, int(groups), _ptr_array(group_param_shards, groups * self.R),
+                                     int(world_worker), _ptr(full_out), _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_gather_hybrid")
+
+    def scatter_accumulate_hybrid(self, groups: int, grad_full, group_accum_shards, world_worker: int,
+                                  microbatch: int, flags: int = ODC_ORDERED, stream=None) -> None:
+        rc = scatter_accumulate_hybrid_rc(self, groups, grad_full, group_accum_shards, world_worker, microbatch,
+                                          flags, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_scatter_accumulate_hybrid")
+
+    def reduce_groups(self, groups: int, group_accum_shards, out_shards, stream=None) -> None:
+        rc = reduce_groups_rc(self, groups, group_accum_shards, out_shards, stream)
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_reduce_groups")
+
     def retrieve_grads(self, accum_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
                        stream=None) -> None:
         rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
@@ -327,6 +359,19 @@ def stage_drain_rc(layout: Layout, staging_shards, flags, snapshot, accum_shards
 def stage_drain_noalloc_rc(layout: Layout, staging_shards, flags, accum_shards, stream=None) -> int:
     return lib().odc_stage_drain_noalloc(layout.handle, _ptr_array(staging_shards, layout.R), _ptr(flags),
                                          _ptr_array(accum_shards, layout.R), _stream(stream))
+
+
+def scatter_accumulate_hybrid_rc(layout: Layout, groups: int, grad_full, group_accum_shards, world_worker: int,
+                                 microbatch: int, flags: int = ODC_ORDERED, stream=None) -> int:
+    return lib().odc_scatter_accumulate_hybrid(layout.handle, int(groups), _ptr(grad_full),
+                                               _ptr_array(group_accum_shards, max(groups, 0) * layout.R),
+                                               int(world_worker), int(microbatch), int(flags), _stream(stream))
+
+
+def reduce_groups_rc(layout: Layout, groups: int, group_accum_shards, out_shards, stream=None) -> int:
+    return lib().odc_reduce_groups(layout.handle, int(groups),
+                                   _ptr_array(group_accum_shards, max(groups, 0) * layout.R),
+                                   _ptr_array(out_shards, layout.R), _stream(stream))
 
 
 def retrieve_grads_rc(layout: Layout, accum_shards, out_shards, scale: float = 1.0,

@@ -452,6 +452,69 @@ int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, v
     return ODC_OK;
 }
 
+// ------------------------------------------------------------------------ hybrid sharding
+int odc_hybrid_group_of(const odc_layout_t *L, int groups, int world_worker)
+{
+    if (!L || groups < 1 || groups > ODC_MAX_GROUPS || world_worker < 0) return -1;
+    const int64_t world = static_cast<int64_t>(groups) * L->host.R;
+    if (world_worker >= world) return -1;
+    return world_worker / L->host.R;
+}
+
+int odc_gather_hybrid(const odc_layout_t *L, int groups, const void *const *group_param_shards, int world_worker,
+                      void *full_out, void *stream)
+{
+    if (!L || !group_param_shards) return ODC_ERR_INVALID_ARG;
+    const int g = odc_hybrid_group_of(L, groups, world_worker);
+    if (g < 0) return ODC_ERR_INVALID_ARG;
+    return odc_gather(L, group_param_shards + static_cast<size_t>(g) * L->host.R, full_out, stream);
+}
+
+int odc_scatter_accumulate_hybrid(const odc_layout_t *L, int groups, const void *grad_full,
+                                  void *const *group_accum_shards, int world_worker, int microbatch, int flags,
+                                  void *stream)
+{
+    if (!L || !group_accum_shards) return ODC_ERR_INVALID_ARG;
+    const int g = odc_hybrid_group_of(L, groups, world_worker);
+    if (g < 0) return ODC_ERR_INVALID_ARG;
+    return odc_scatter_accumulate(L, grad_full, group_accum_shards + static_cast<size_t>(g) * L->host.R,
+                                  world_worker % L->host.R, microbatch, flags, stream);
+}
+
+int odc_reduce_groups(const odc_layout_t *L, int groups, const void *const *group_accum_shards,
+                      void *const *out_shards, void *stream)
+{
+    if (!L || !group_accum_shards || groups < 1 || groups > ODC_MAX_GROUPS) return ODC_ERR_INVALID_ARG;
+    int rc = check_launchable(L, out_shards);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    const int R = H.R;
+    for (int k = 0; k < groups; ++k) {
+        rc = check_launchable(L, group_accum_shards + static_cast<size_t>(k) * R);
+        if (rc != ODC_OK) return rc;
+    }
+    // the sum may replace group 0's shards; a later group's shard would be overwritten by the
+    // first pass before a later pass reads it
+    for (int k = 1; k < groups; ++k)
+        for (int r = 0; r < R; ++r)
+            for (int q = 0; q < R; ++q)
+                if (group_accum_shards[static_cast<size_t>(k) * R + r] == out_shards[q]) return ODC_ERR_INVALID_ARG;
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::BatchTable *tb = H.T == 1 ? nullptr : &L->table;
+    for (int r0 = 0; r0 < R; r0 += odc::kReduceRanksPerLaunch) {
+        const int nr = R - r0 < odc::kReduceRanksPerLaunch ? R - r0 : odc::kReduceRanksPerLaunch;
+        for (int k0 = 0; k0 < groups; k0 += odc::kReduceSourcesPerPass) {
+            const int count = groups - k0 < odc::kReduceSourcesPerPass ? groups - k0 : odc::kReduceSourcesPerPass;
+            const int e = odc::launch_reduce_groups(tb, group_accum_shards + static_cast<size_t>(k0) * R + r0, R, count,
+                                                    k0 == 0, out_shards + r0, r0, nr, H.desc[0].S, H.desc[0].numel,
+                                                    stream);
+            if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+        }
+    }
+    return ODC_OK;
+}
+
 int odc_reset_accum(const odc_layout_t *L, void *const *accum_shards, void *stream)
 {
     int rc = check_launchable(L, accum_shards);

@@ -154,6 +154,11 @@ int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int n
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,
                             float scale, bool bf16, void *stream);
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream);
+// Hybrid sharding: one pass of the sum over groups (tb = nullptr: single tensor with S, N).
+constexpr int kReduceSourcesPerPass = 8;
+constexpr int kReduceRanksPerLaunch = 16;
+int launch_reduce_groups(const BatchTable *tb, const void *const *srcs, int64_t stride, int count, bool init,
+                         void *const *outs, int r0, int nr, int64_t S, int64_t N, void *stream);
 int launch_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
 
 }  // namespace odc

@@ -368,6 +368,50 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
     return finish();
 }
 
+// One pass of the group reduction: owners [r0, r0 + nr), nr <= kReduceRanks; `count` sources per
+// owner (1..kReduceSources), srcs[k * stride + r] = source k of owner r0 + r; init: the sum starts
+// from the first source instead of the stored value of out.
+static_assert(kReduceSources == kReduceSourcesPerPass && kReduceRanks == kReduceRanksPerLaunch,
+              "the host loop and the kernels must agree on the pass shape");
+
+int launch_reduce_groups(const BatchTable *tb, const void *const *srcs, int64_t stride, int count, bool init,
+                         void *const *outs, int r0, int nr, int64_t S, int64_t N, void *stream)
+{
+    ReducePtrs p{};
+    for (int r = 0; r < kReduceRanks; ++r) {
+        for (int k = 0; k < kReduceSources; ++k)
+            p.src[r][k] = static_cast<const float *>(r < nr && k < count ? srcs[k * stride + r] : nullptr);
+        p.out[r] = static_cast<float *>(r < nr ? outs[r] : nullptr);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define ODC_REDUCE(K_, INIT_)                                                                                  \
+    do {                                                                                                       \
+        if (tb) {                                                                                              \
+            const dim3 grid(batched_grid_x((tb->arena_elems + kChunkElems - 1) >> kChunkShift),                 \
+                            static_cast<unsigned>(nr));                                                        \
+            k_reduce_batched<K_, INIT_><<<grid, kBatchThreads, 0, s>>>(*tb, p, r0);                              \
+        } else {                                                                                               \
+            k_reduce_flat<K_, INIT_><<<plain_grid((S >> 2) + 1, 64, nr), 64, 0, s>>>(p, S, N, r0);               \
+        }                                                                                                      \
+    } while (0)
+#define ODC_REDUCE_K(INIT_)                               \
+    switch (count) {                                      \
+        case 1: ODC_REDUCE(1, INIT_); break;              \
+        case 2: ODC_REDUCE(2, INIT_); break;              \
+        case 3: ODC_REDUCE(3, INIT_); break;              \
+        case 4: ODC_REDUCE(4, INIT_); break;              \
+        case 5: ODC_REDUCE(5, INIT_); break;              \
+        case 6: ODC_REDUCE(6, INIT_); break;              \
+        case 7: ODC_REDUCE(7, INIT_); break;              \
+        default: ODC_REDUCE(8, INIT_); break;             \
+    }
+    if (init) ODC_REDUCE_K(true)
+    else ODC_REDUCE_K(false)
+#undef ODC_REDUCE_K
+#undef ODC_REDUCE
+    return finish();
+}
+
 // ------------------------------------------------------------------ fixed scratch, no allocation
 // Snapshot list of odc_stage_drain_noalloc: lives in the code object, one copy per GPU, so the
 // entry point needs no workspace from the caller and never allocates.  The array's name is

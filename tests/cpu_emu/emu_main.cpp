@@ -476,6 +476,67 @@ int main(int argc, char **argv)
         return 0;
     }
 
+    if (op == "reduce") {
+        // groups.f32 [count * R * arena] group-major; out.f32 [R * arena] in/out; inplace=1: the
+        // output buffers are group 0's (out.f32 is then ignored on input)
+        const int K = count;
+        std::vector<float> all = read_file<float>(dir + "/groups.f32");
+        std::vector<float> out_in = read_file<float>(dir + "/out.f32");
+        if (K < 1 || all.size() != arena * static_cast<size_t>(R) * K || out_in.size() != arena * static_cast<size_t>(R)) return 4;
+        std::vector<float *> srcs(static_cast<size_t>(R) * K), outs(static_cast<size_t>(R));
+        for (size_t q = 0; q < srcs.size(); ++q) {
+            srcs[q] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(srcs[q], all.data() + arena * q, arena * 4);
+        }
+        for (int r = 0; r < R; ++r) {
+            if (lds_max) outs[r] = srcs[r];  // reuse of the flag: in place into group 0
+            else {
+                outs[r] = static_cast<float *>(std::malloc(arena * 4));
+                std::memcpy(outs[r], out_in.data() + arena * r, arena * 4);
+            }
+        }
+        for (int r0 = 0; r0 < R; r0 += kReduceRanks) {
+            const int nr = R - r0 < kReduceRanks ? R - r0 : kReduceRanks;
+            for (int k0 = 0; k0 < K; k0 += kReduceSources) {
+                const int cnt = K - k0 < kReduceSources ? K - k0 : kReduceSources;
+                ReducePtrs p{};
+                for (int r = 0; r < nr; ++r) {
+                    for (int k = 0; k < cnt; ++k) p.src[r][k] = srcs[static_cast<size_t>(k0 + k) * R + r0 + r];
+                    p.out[r] = outs[r0 + r];
+                }
+#define EMU_REDUCE(K_, INIT_)                                                                                        \
+    do {                                                                                                             \
+        if (flat) run_grid(64, grid_x_for((S >> 2) + 1, 64, cap), nr, [&] { k_reduce_flat<K_, INIT_>(p, S, N, r0); }); \
+        else                                                                                                         \
+            run_grid_threaded(kBatchThreads, grid_x_for((tb.arena_elems + kChunkElems - 1) >> kChunkShift, 1, cap),  \
+                              static_cast<unsigned>(nr), [&] { k_reduce_batched<K_, INIT_>(tb, p, r0); });           \
+    } while (0)
+#define EMU_REDUCE_K(INIT_)                          \
+    switch (cnt) {                                   \
+        case 1: EMU_REDUCE(1, INIT_); break;         \
+        case 2: EMU_REDUCE(2, INIT_); break;         \
+        case 3: EMU_REDUCE(3, INIT_); break;         \
+        case 4: EMU_REDUCE(4, INIT_); break;         \
+        case 5: EMU_REDUCE(5, INIT_); break;         \
+        case 6: EMU_REDUCE(6, INIT_); break;         \
+        case 7: EMU_REDUCE(7, INIT_); break;         \
+        default: EMU_REDUCE(8, INIT_); break;        \
+    }
+                if (k0 == 0) EMU_REDUCE_K(true)
+                else EMU_REDUCE_K(false)
+#undef EMU_REDUCE_K
+#undef EMU_REDUCE
+            }
+        }
+        std::vector<float> out(arena * static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) std::memcpy(out.data() + arena * r, outs[r], arena * 4);
+        write_file(dir + "/out.out", out.data(), out.size());
+        if (!lds_max)
+            for (auto *b : outs) std::free(b);
+        for (auto *b : srcs) std::free(b);
+        return 0;
+    }
+
     if (op == "retrieve") {
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;

@@ -261,6 +261,29 @@ def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
     assert flags[R * R] == model.refused and model.refused >= R     # at least the second push of worker 0
 
 
+@pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([4099], 20), ([1], 64),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5),
+                                     ([5] * 34, 34), ([40_000, 9, 20_001, 3], 2)])
+@pytest.mark.parametrize("K,inplace", [(1, 0), (2, 1), (8, 0), (9, 1), (19, 0)])
+def test_emulated_reduce_groups(oracle, emu, tmp_path, numel, R, K, inplace):
+    """Hybrid sharding: the sum of K groups' accumulator shards (one, two and three passes of up
+    to 8 sources; more than 16 owners = two launches), into a separate output or in place into
+    group 0; everything compared with the oracle, sentinels in padding and gaps included."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    rng = np.random.default_rng(K * 100 + R)
+    groups = [[(rng.standard_normal(arena) * 1e-2).astype(np.float32) for _ in range(R)] for _ in range(K)]
+    out = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    np.concatenate([a for grp in groups for a in grp]).tofile(tmp_path / "groups.f32")
+    np.concatenate(out).tofile(tmp_path / "out.f32")
+    run(emu, tmp_path, "reduce", R, count=K, lds_max=inplace)
+    got = np.fromfile(tmp_path / "out.out", dtype=np.float32)
+    want = [g.copy() for g in groups[0]] if inplace else out
+    src = [want] + groups[1:] if inplace else groups
+    oracle.reduce_groups_batched(src, want, numel, so)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(want).view(np.uint32))
+
+
 INTERLEAVINGS = [
     # a client pushes again while its slot is full; a drain on another stream empties the slot
     # after the claim / between the copy workgroups / before the raise
