@@ -155,7 +155,9 @@ int odc_scatter_accumulate_weighted(const odc_layout_t *layout, const void *grad
  *   workers, microbatches  [count] host arrays; in ODC_ORDERED mode strictly ascending
  *                 (worker, microbatch) pairs, the first one after this accumulator set's history
  *                 (ODC_ERR_ORDER otherwise, nothing enqueued); the history becomes the last pair.
- *   ODC_UNORDERED sums the count values in registers and issues one atomic add per element.
+ *   ODC_UNORDERED sums the count values in registers as a balanced binary tree (pairwise) and
+ *                 issues one atomic add per element: C contributions taken `count` at a time pass
+ *                 through ceil(log2 count) + ceil(C / count) roundings instead of C.
  */
 #define ODC_MAX_FUSED 8
 int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const void *const *grads,

@@ -301,7 +301,27 @@ def widen(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def fp64_sum_shards(grads, N: int, R: int):
+def fp64_add(g: np.ndarray, tot: np.ndarray, mag: np.ndarray, nthreads: int = 1, ranges=None) -> None:
+    """One contribution added to a float64 reference: tot[j] += widen(g[j]), mag[j] += |widen(g[j])|
+    for every j (or only inside the given [a, b) intervals).  tot and mag are float64 arrays as
+    long as g; the element range may be split over threads."""
+    n = g.shape[0]
+    _check(g, np.uint16, n, "g")
+    _check(tot, np.float64, n, "tot")
+    _check(mag, np.float64, n, "mag")
+
+    def part(a, b):
+        step = 1 << 22                                   # bounded temporaries
+        for lo in range(a, b, step):
+            hi = min(b, lo + step)
+            v = widen(g[lo:hi]).astype(np.float64)
+            tot[lo:hi] += v
+            mag[lo:hi] += np.abs(v)
+
+    _run_ranges(part, n, nthreads, ranges)
+
+
+def fp64_sum_shards(grads, N: int, R: int, nthreads: int = 1):
     """Reference for the unordered mode: per owner, the float64 sum of all contributions.
 
     Returns (sum64, abs64): lists of R float64 arrays of S slots (padding = 0) holding
@@ -313,9 +333,7 @@ def fp64_sum_shards(grads, N: int, R: int):
     mag = np.zeros(R * S, dtype=np.float64)
     for per_worker in grads:
         for g in per_worker:
-            v = widen(g[:N]).astype(np.float64)
-            tot[:N] += v
-            mag[:N] += np.abs(v)
+            fp64_add(np.ascontiguousarray(g[:N]), tot[:N], mag[:N], nthreads)
     return ([tot[r * S:(r + 1) * S] for r in range(R)],
             [mag[r * S:(r + 1) * S] for r in range(R)])
 

@@ -982,7 +982,8 @@ __global__ __launch_bounds__(kBatchThreads) void k_reset_batched(BatchTable tb, 
 // the ordered result is bit-identical -- but the accumulator is read and written once:
 // (2K + 8) bytes per element instead of 10K.  Fixed launch shape: one wavefront per
 // workgroup, one accumulator vector per lane, non-temporal accesses.  The unordered form sums
-// the K values in registers and issues one atomic add per element.
+// the K values in registers, pairwise, and issues one atomic add per element: C contributions
+// taken K at a time go through ceil(log2 K) + ceil(C / K) roundings instead of C.
 
 constexpr int kMaxFused = 8;
 
@@ -1013,17 +1014,27 @@ __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const G
     }
 }
 
-// Sum of the K values of one element, left to right (unordered form: added atomically).
+// Sum of values v[lo .. lo + n) as a balanced binary tree (pairwise summation): the rounding
+// error of the sum grows with the depth ceil(log2 n) of the tree instead of with n.
+template <int N0>
+__device__ __forceinline__ float tree_sum(const float *v)
+{
+    if constexpr (N0 == 1) return v[0];
+    else return tree_sum<N0 - N0 / 2>(v) + tree_sum<N0 / 2>(v + (N0 - N0 / 2));
+}
+
+// Sum of the K values of one element for the unordered form (added atomically afterwards).  No
+// order is promised there, so the association that bounds the error best is used: pairwise.
 template <int K>
 __device__ __forceinline__ float multi_sum_one(const GradPtrs &grads, int64_t goff, int64_t e)
 {
     uint16_t gv[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) gv[k] = ld_u16(grads.p[k] + goff + e);
-    float sum = widen_one(gv[0]);
+    float v[K];
 #pragma unroll
-    for (int k = 1; k < K; ++k) sum = sum + widen_one(gv[k]);
-    return sum;
+    for (int k = 0; k < K; ++k) v[k] = widen_one(gv[k]);
+    return tree_sum<K>(v);
 }
 
 template <int K, bool ATOMIC>

@@ -227,6 +227,29 @@ def test_emulated_fused_accumulate(oracle, emu, tmp_path, numel, R, count, cap):
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
 
 
+@pytest.mark.parametrize("numel,R", [([8 * 1024 * 3 + 5], 4), ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
+                                     ([5] * 66, 66)])
+@pytest.mark.parametrize("count", [2, 3, 5, 7, 8])
+def test_emulated_fused_unordered_sums_every_gradient_once(oracle, emu, tmp_path, numel, R, count):
+    """The unordered fused form adds the K values of an element as a binary tree.  With
+    integer-valued gradients every association gives the same exact sum, so the result must
+    equal K single contributions bit for bit: a value dropped or counted twice by the tree
+    would show."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    oracle.reset_batched(acc, numel, so)
+    np.concatenate(acc).tofile(tmp_path / "acc.f32")
+    rng = np.random.default_rng(count)
+    for k in range(count):
+        g = inputs.f32_to_bf16_bits((rng.integers(-100, 101, size=full_n) * 3 ** k % 251).astype(np.float32))
+        g.tofile(tmp_path / f"grad{k}.u16")
+        oracle.accumulate_batched(g, acc, numel, so, fo)
+    run(emu, tmp_path, "accum_multi", R, count=count, atomic=1)
+    got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
+
+
 @pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([4099], 8), ([1], 64),
                                      ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5),
                                      ([5] * 66, 66), ([40_000, 9, 20_001, 3], 2)])

@@ -524,3 +524,25 @@ def test_staging_model_phases(oracle):
     for k in (0, 3, 1):                  # first drain: client 0; second: client 0 before client 1
         oracle.accumulate(gs[k], ref, N)
     assert same(acc, ref)
+
+
+def test_fp64_reference_is_the_exact_rational_sum_on_small_cases(oracle):
+    """The float64 reference of the unordered mode against exact rational arithmetic: bf16 values
+    of similar magnitude add without rounding in float64, so tot must equal the exact sum and mag
+    the exact sum of magnitudes; elements outside the given ranges stay untouched."""
+    from fractions import Fraction
+
+    n, C = 64, 7
+    gs = [inputs.normal_bf16(n, 1e-3, seed=(72, k)) for k in range(C)]
+    tot, mag = np.zeros(n), np.zeros(n)
+    for g in gs:
+        oracle.fp64_add(g, tot, mag, nthreads=3)
+    for j in range(n):
+        vals = [Fraction(float(oracle.widen(g[j:j + 1])[0])) for g in gs]
+        assert Fraction(float(tot[j])) == sum(vals)
+        assert Fraction(float(mag[j])) == sum(abs(v) for v in vals)
+    tot2, mag2 = np.zeros(n), np.zeros(n)
+    oracle.fp64_add(gs[0], tot2, mag2, ranges=[(3, 9), (40, 41)])
+    keep = np.zeros(n, dtype=bool)
+    keep[3:9] = keep[40:41] = True
+    assert (tot2[~keep] == 0).all() and np.array_equal(tot2[keep], oracle.widen(gs[0]).astype(np.float64)[keep])
