@@ -581,6 +581,8 @@ int odc_tune(const char *knob, int value)
     else if (!std::strcmp(knob, "tile_remap") && flag_ok) t.tile_remap = value;
     else if (!std::strcmp(knob, "gather_store_sc1") && flag_ok) t.gather_store_sc1 = value;
     else if (!std::strcmp(knob, "max_grid_x") && value >= 0) t.max_grid_x = value;
+    else if (!std::strcmp(knob, "gather_tile_xcd_block") && value >= 1 && value <= 4096 && (value & (value - 1)) == 0)
+        t.gather_tile_xcd_block = value;
     else if (!std::strcmp(knob, "batch_rank_group") &&
              (value == 0 || value == 1 || value == 2 || value == 4 || value == 8))
         t.batch_rank_group = value;

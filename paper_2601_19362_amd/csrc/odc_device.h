@@ -366,6 +366,14 @@ __global__ __launch_bounds__(TPB) void k_reset_flat(RankPtrs accs, int64_t S, in
 // A tile that lies inside one tensor skips all of that, and if all of it is valid for the
 // owners at hand (tile_is_uniform) it runs the plain vector loop of the single-tensor kernels.
 
+// Loads of short shard pieces (a gradient slice or a parameter piece of a small tensor) do NOT
+// carry the non-temporal hint in the multi-tensor kernels: neighbouring pieces share cache
+// lines, neighbouring wavefronts read them at slightly different times, and a line loaded with
+// the streaming hint is dropped from the L2 before its neighbour arrives and is fetched from
+// memory again (stress workload: batched gather 59 -> 48 us from this alone).  Dense streams --
+// accumulators, whole-tile paths of large tensors, all stores -- keep the hint.
+constexpr bool kPieceLoadsNT = false;
+
 constexpr int kChunkElems = 1 << kChunkShift;
 constexpr int kBatchThreads = 256;
 constexpr int kAccumItems = kChunkElems / (4 * kBatchThreads);  // accumulate tile: 1 chunk
@@ -434,6 +442,18 @@ __device__ __forceinline__ bool tile_is_uniform(const TensorDesc &d, int64_t a0,
     int64_t valid = d.numel - static_cast<int64_t>(r_first + count - 1) * d.S;  // the last owner has the fewest
     if (valid > d.S) valid = d.S;
     return a0 >= d.shard_off && a0 - d.shard_off + tile_elems <= valid;
+}
+
+// Work order of the gather kernels.  Consecutive workgroup ids go to the 8 XCDs in turn, and
+// each XCD has its own L2.  The shard pieces that neighbouring tiles read sit next to each other
+// in every owner's arena and share cache lines, so work units are handed out in blocks: of every
+// 8 * block consecutive units, XCD x takes units [x * block, (x + 1) * block), which keeps the
+// lines that neighbours share inside one L2 instead of fetching them once per XCD.
+// `shift` = log2(block); slot = workgroup id.
+__device__ __forceinline__ int64_t span_of(int64_t slot, int shift)
+{
+    const int64_t x = slot & 7, q = slot >> 3;
+    return ((q >> shift) << (shift + 3)) + (x << shift) + (q & ((int64_t{1} << shift) - 1));
 }
 
 // ---- gather, full-buffer-major ---------------------------------------------------------
@@ -614,7 +634,8 @@ __device__ __forceinline__ int gather_find(const GatherTile<CAP> &lds, int n, in
 // and copied element-wise, one lane per element, by the loop at the end of the kernel.
 template <bool NT, int CAP, bool BIG>
 __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
-                                                                  uint16_t *__restrict__ full, int r0, int nr)
+                                                                  uint16_t *__restrict__ full, int r0, int nr,
+                                                                  int block_shift)
 {
     constexpr int UG = 2;  // items in flight per thread
     static_assert(kGatherChunks % UG == 0, "tile must hold a whole number of item groups");
@@ -622,8 +643,11 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
     if (threadIdx.x < kRanksPerLaunch) lds.base[threadIdx.x] = arenas.p[threadIdx.x];
     const int64_t nchunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t ntiles = (nchunks + kGatherChunks - 1) / kGatherChunks;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        if (tile != static_cast<int64_t>(blockIdx.x)) __syncthreads();  // LDS reuse across iterations
+    const int64_t nslots = ((ntiles + (int64_t{8} << block_shift) - 1) >> (block_shift + 3)) << (block_shift + 3);
+    for (int64_t slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
+        if (slot != static_cast<int64_t>(blockIdx.x)) __syncthreads();  // LDS reuse across iterations
+        const int64_t tile = span_of(slot, block_shift);  // tiles handed to the XCDs in blocks
+        if (tile >= ntiles) continue;
         const int64_t c0 = tile * kGatherChunks;
         const int64_t c1 = c0 + kGatherChunks < nchunks ? c0 + kGatherChunks : nchunks;
         const int64_t a0 = c0 << kChunkShift;
@@ -701,9 +725,10 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
                 }
                 const uint32_t e_lo = in_a ? 0u : split;
                 const uint32_t e_hi = (split != 0 && !in_b) ? split : cnt;
-                if (in_a) va[u] = ld_u128_unaligned<NT>(static_cast<const uint16_t *>(lds.base[rl]) + shard_off + i);
+                constexpr bool NTL = NT && kPieceLoadsNT;
+                if (in_a) va[u] = ld_u128_unaligned<NTL>(static_cast<const uint16_t *>(lds.base[rl]) + shard_off + i);
                 if (in_b)
-                    vb[u] = ld<NT>(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(lds.base[rl + 1]) +
+                    vb[u] = ld<NTL>(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(lds.base[rl + 1]) +
                                                                    shard_off));
                 code[u] = kGatherWide | static_cast<int>(split << 4 | e_lo << 8 | e_hi << 12);
             }
@@ -782,7 +807,7 @@ __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc 
     const int64_t goff = d.full_off + static_cast<int64_t>(r) * d.S + slot;
     const uint16_t *gp = grad + goff;
     if (it.cnt == 4 || (a + 4 <= arena_elems && goff + 4 <= full_elems)) {
-        it.g = ld_u64_unaligned<NT>(gp);
+        it.g = ld_u64_unaligned<NT && kPieceLoadsNT>(gp);
         it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(ap));
     } else {
         const uint32_t e0 = ld_u16(gp);
@@ -815,6 +840,9 @@ __device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap,
 // first, so consecutive workgroups sweep one owner group's arenas from start to end and the
 // chip works on a few advancing address windows at a time (measurably faster than spreading
 // every tile over all owners first); and no kernel has to divide a linear work index.
+// (Also measured and rejected: blocks of 8 to 128 tiles with the owner groups taken in turn
+// inside a block, so that the gradient lines two neighbouring owners share stay in one L2: 10 %
+// slower on the many-small-tensor workload.  Long contiguous runs per owner matter more.)
 template <int RG, bool NT, bool ATOMIC, bool WEIGHTED>
 __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG == 2 ? 8 : 1) void k_accum_batched(BatchTable tb, RankPtrs accs,
                                                                  const uint16_t *__restrict__ grad, int r0, int nr,
@@ -994,13 +1022,13 @@ struct GradPtrs {
 // One accumulator vector (ordered form); `cnt` < 4 marks a ragged item whose loads are still
 // wide (the caller has checked that they stay inside the buffers) and whose first cnt results
 // are kept.
-template <int K>
+template <int K, bool NTG = true>
 __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q,
                                                 int cnt = 4)
 {
     u32x2 gv[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) gv[k] = ld_u64_unaligned<true>(grads.p[k] + goff + 4 * q);
+    for (int k = 0; k < K; ++k) gv[k] = ld_u64_unaligned<NTG>(grads.p[k] + goff + 4 * q);
     f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
     f32x4 a = ld<true>(av);
 #pragma unroll
@@ -1129,10 +1157,9 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
             const int cnt = valid_from(d, r0 + rl, slot, 4);
             // gradient element that pairs with arena element a: goff + a
             const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
-            // a ragged item keeps the wide loads only for K <= 2 (measured: beyond that the
-            // element-wise form is faster)
-            if (cnt == 4 || (K <= 2 && cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
-                accum_multi_vec<K>(arena, grads, goff, a >> 2, cnt);
+            // a ragged item keeps the wide loads wherever they stay inside the buffers
+            if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
+                accum_multi_vec<K, kPieceLoadsNT>(arena, grads, goff, a >> 2, cnt);
             else
                 for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
         }
@@ -1274,7 +1301,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
                 // a ragged end (c < 8) keeps the wide load: the extra lanes belong to the next
                 // piece and are dropped
                 cnt[u] = c;
-                v[u] = ld_u128_unaligned<NT>(grad + goff);
+                v[u] = ld_u128_unaligned<NT && kPieceLoadsNT>(grad + goff);
             } else {  // the last elements of the gradient buffer
                 for (int e = 0; e < c; ++e) st_u16(dst + a + e, ld_u16(grad + goff + e));
             }

@@ -149,13 +149,16 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
 {
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    uint16_t *out = static_cast<uint16_t *>(full);
     const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
-    const dim3 grid(batched_grid_x(tiles));
-    uint16_t *out = static_cast<uint16_t *>(full);
+    int tshift = 0;
+    while ((1 << tshift) < tuning().gather_tile_xcd_block) ++tshift;
+    const int64_t tgroup = int64_t{8} << tshift;
+    const dim3 grid(batched_grid_x((tiles + tgroup - 1) / tgroup * tgroup));
 #define ODC_GATHER_BATCHED(CAP_, BIG_)                                 \
     ODC_DISPATCH_NT(tuning().nontemporal != 0,                         \
-                    (k_gather_batched<NT_, CAP_, BIG_><<<grid, kBatchThreads, 0, s>>>(tb, rp, out, r0, nr)))
+                    (k_gather_batched<NT_, CAP_, BIG_><<<grid, kBatchThreads, 0, s>>>(tb, rp, out, r0, nr, tshift)))
     const bool few = tb.gather_tile_tensors <= kGatherFewTensors;
     if (few && tb.gather_big) ODC_GATHER_BATCHED(kGatherFewTensors, true);
     else if (few) ODC_GATHER_BATCHED(kGatherFewTensors, false);

@@ -218,15 +218,19 @@ int main(int argc, char **argv)
             } else {
                 const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
                 const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
+                // remap > 0 for a multi-tensor layout: tiles handed out in XCD blocks of 2^remap
+                const int tshift = remap;
+                const int64_t tgroup = int64_t{8} << tshift;
+                const unsigned tgx = grid_x_for((tiles + tgroup - 1) / tgroup * tgroup, 1, cap);
                 if (tb.gather_tile_tensors <= kGatherFewTensors && !lds_max) {
-                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
-                               if (tb.gather_big) k_gather_batched<NT_, kGatherFewTensors, true>(tb, rp, full, r0, nr);
-                               else k_gather_batched<NT_, kGatherFewTensors, false>(tb, rp, full, r0, nr);
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, tgx, 1, [&] {
+                               if (tb.gather_big) k_gather_batched<NT_, kGatherFewTensors, true>(tb, rp, full, r0, nr, tshift);
+                               else k_gather_batched<NT_, kGatherFewTensors, false>(tb, rp, full, r0, nr, tshift);
                            }));
                 } else {
-                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), 1, [&] {
-                               if (tb.gather_big) k_gather_batched<NT_, kGatherMaxTensors, true>(tb, rp, full, r0, nr);
-                               else k_gather_batched<NT_, kGatherMaxTensors, false>(tb, rp, full, r0, nr);
+                    EMU_NT(nt, run_grid_threaded(kBatchThreads, tgx, 1, [&] {
+                               if (tb.gather_big) k_gather_batched<NT_, kGatherMaxTensors, true>(tb, rp, full, r0, nr, tshift);
+                               else k_gather_batched<NT_, kGatherMaxTensors, false>(tb, rp, full, r0, nr, tshift);
                            }));
                 }
             }

@@ -397,7 +397,7 @@ def test_emulated_random_layouts(oracle, emu, emu_low_limit, tmp_path, seed):
     oracle.gather_batched(arenas, numel, so, fo, want)
     for exe in (emu, emu_low_limit):
         np.full(full_n, 0xBEEF, dtype=np.uint16).tofile(tmp_path / "full.u16")
-        run(exe, tmp_path, "gather", R, nt=seed % 2)
+        run(exe, tmp_path, "gather", R, nt=seed % 2, remap=seed % 5)   # tiles in XCD blocks of 1 .. 16
         assert np.array_equal(np.fromfile(tmp_path / "full.out", dtype=np.uint16), want), (numel, R)
 
     acc = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
