@@ -50,20 +50,26 @@ def parse_args():
     return ap.parse_args()
 
 
+PROFILE_OF = {"7b": "odc_kernels_7b_workload.md", "1.5b": "odc_kernels_1p5b_workload.md",
+              "32b": "odc_kernels_32b_workload.md", "stress": "odc_kernels_stress_workload.md"}
+
+
 def recorded_traffic(workload, tune):
     """HBM bytes per accumulate launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (scaled by a plain copy of known size) and written down in profiles/; None if the run is
-    not the configuration that summary covers."""
-    if workload != "7b" or tune:
-        return None
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "odc_kernels_7b_workload.md")
+    (scaled by a plain copy of known size) in an earlier run of this same command and written
+    down in profiles/.  Returns (bytes, source); (None, reason) if the run is not a configuration
+    a summary covers.  The counters cannot be read from inside this process, so the figure is a
+    recorded one and the bench line says so."""
+    if tune or workload not in PROFILE_OF:
+        return None, "not measured (no recorded counter run for this workload / tuning)"
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", PROFILE_OF[workload])
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+                return float(line.split("=")[1]), f"recorded: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs in profiles/{PROFILE_OF[workload]}, not this run"
     except OSError:
         pass
-    return None
+    return None, "not measured (profile summary not found)"
 
 
 def build_state(w, layers, torch, odc, inputs):
@@ -328,6 +334,10 @@ def main():
         acc_ms = acc_med
     achieved = 10 * total / (acc_ms * 1e-3) / 1e9
 
+    if args.traffic_bytes is not None:
+        traffic, traffic_source = args.traffic_bytes, "given on the command line (--traffic-bytes)"
+    else:
+        traffic, traffic_source = recorded_traffic(args.workload, args.tune)
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
@@ -347,8 +357,7 @@ def main():
             "bound": "hbm", "kernel": "scatter_accumulate (ordered)",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": (args.traffic_bytes if args.traffic_bytes is not None
-                        else recorded_traffic(args.workload, args.tune)),
+            "traffic": traffic, "traffic_source": traffic_source,
             "avg_launch_ms": round(acc_ms, 4), "launches_timed": (len(events.pairs) if events else 0),
             "algorithmic_bytes_per_launch": 10 * total,
         },

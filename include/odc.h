@@ -22,9 +22,14 @@
  *     gradient) must be 16-byte aligned, else ODC_ERR_ALIGNMENT.  Interior boundaries
  *     (r * S_t) may fall anywhere; that is the library's business.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Launch
- *     calls only enqueue work on it and return: they never synchronise, allocate or free.
+ *     calls only enqueue work on it and return: they never synchronise the device and never
+ *     allocate or free device memory.  On the host, the ordered mode takes the layout's mutex
+ *     for the duration of the call and, the first time it sees an accumulator set, allocates
+ *     one small bookkeeping node (see ODC_ORDERED below); nothing else allocates.
  *     A call enqueues one kernel per group of up to 64 ranks, so exactly one kernel for
- *     R <= 64, for any number of tensors T.
+ *     R <= 64, for any number of tensors T.  With R > 64, if a later group's launch fails
+ *     (ODC_ERR_HIP) the earlier groups' kernels are already enqueued: the accumulators are then
+ *     partly updated, and the contribution counts as issued.
  *   - Return value: ODC_OK (0) or a negative ODC_ERR_* code.  All argument errors are
  *     detected on the host before anything is enqueued.  Nothing throws or aborts.
  *   - Padding (shard slots whose flat index is >= numel) is never read into a result and
@@ -116,7 +121,13 @@ int odc_gather(const odc_layout_t *layout, const void *const *param_shards, void
  *                 contributions of one accumulator set in that order on one stream.  The library
  *                 remembers the last (worker, microbatch) per (layout, accum_shards[0]) and
  *                 returns ODC_ERR_ORDER, enqueuing nothing, if a call is not strictly later;
- *                 odc_reset_accum forgets it.  Two ordered calls on the same accumulators
+ *                 odc_reset_accum and odc_forget_accum forget it, and so does freeing the
+ *                 layout.  The table holds at most 1024 accumulator sets per layout; beyond
+ *                 that the least recently used entry is dropped (that set then starts afresh).
+ *                 The key is an address: accumulators that are freed without a reset and whose
+ *                 address is handed out again would inherit the old history -- call
+ *                 odc_forget_accum (or odc_reset_accum) before freeing or after reallocating.
+ *                 Two ordered calls on the same accumulators
  *                 running concurrently on different streams race (caller error).
  *                 ODC_UNORDERED: each element is added with a device-scope float atomic add
  *                 (no order check); concurrent calls on several streams are safe, the result
@@ -296,6 +307,13 @@ int odc_reduce_groups(const odc_layout_t *layout, int groups, const void *const 
  */
 int odc_reset_accum(const odc_layout_t *layout, void *const *accum_shards, void *stream);
 
+/*
+ * Drop the ordered-mode history of an accumulator set without touching the accumulators (host
+ * only, nothing enqueued): for accumulators that are about to be freed, or whose address has
+ * just been handed out again.  Returns ODC_OK whether or not a history existed.
+ */
+int odc_forget_accum(const odc_layout_t *layout, void *const *accum_shards);
+
 /* Text for an ODC_* code (static string, never NULL). */
 const char *odc_strerror(int code);
 
@@ -307,7 +325,8 @@ int odc_last_hip_error(void);
  * odc_probe_copy: plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both
  * pointers 16-byte aligned) on `stream`: a kernel of known traffic used to calibrate
  * hardware counters and to measure this GPU's copy ceiling next to the ODC kernels.
- * odc_tune: set a launch knob by name for all later calls of this process:
+ * odc_tune: set a launch knob by name for all later calls of this process (safe to call while
+ * other threads launch: every launch works from one consistent copy of the knobs):
  *   "gather_threads" / "accum_threads" / "reset_threads"  workgroup size of the single-tensor
  *                                                          kernels: 64, 128 or 256
  *   "gather_unroll" / "accum_unroll" / "reset_unroll"     16-byte work items per thread: 1, 2, 4

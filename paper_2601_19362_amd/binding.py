@@ -35,7 +35,7 @@ EXPORTS = (
     "odc_init_layout", "odc_free_layout", "odc_num_ranks", "odc_num_tensors", "odc_numel",
     "odc_shard_elems", "odc_valid_elems", "odc_rank_arena_elems", "odc_full_elems",
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
-    "odc_reset_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
+    "odc_reset_accum", "odc_forget_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
     "odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count", "odc_stage_init",
     "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_hybrid_group_of",
     "odc_gather_hybrid", "odc_scatter_accumulate_hybrid", "odc_reduce_groups", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
@@ -118,6 +118,8 @@ def lib():
         L.odc_retrieve_grads.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_reset_accum.restype = _int
         L.odc_reset_accum.argtypes = [_vp, ctypes.POINTER(_vp), _vp]
+        L.odc_forget_accum.restype = _int
+        L.odc_forget_accum.argtypes = [_vp, ctypes.POINTER(_vp)]
         L.odc_strerror.restype = ctypes.c_char_p
         L.odc_strerror.argtypes = [_int]
         L.odc_last_hip_error.restype = _int
@@ -316,6 +318,11 @@ class Layout:
         rc = retrieve_grads_rc(self, accum_shards, out_shards, scale, out_dtype, stream)
         if rc != ODC_OK:
             raise OdcError(rc, "odc_retrieve_grads")
+
+    def forget_accum(self, accum_shards) -> None:
+        rc = lib().odc_forget_accum(self._h, _ptr_array(accum_shards, self.R))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_forget_accum")
 
     def reset_accum(self, accum_shards, stream=None) -> None:
         rc = reset_accum_rc(self, accum_shards, stream)

@@ -35,11 +35,43 @@ int check_launchable(const odc_layout_t *L, const void *const *ptrs)
 int check_device(const odc_layout_t *L)
 {
     if (L->host_only) return ODC_ERR_NO_DEVICE;
+    // With a single visible device the current device cannot differ from the layout's: the
+    // count is read once per process and the per-call query is skipped.
+    static const int n_devices = [] {
+        int n = 0;
+        return hipGetDeviceCount(&n) == hipSuccess ? n : 0;
+    }();
+    if (n_devices == 1) return ODC_OK;
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
     if (dev != L->device) return ODC_ERR_NO_DEVICE;
     return ODC_OK;
+}
+
+// Ordered-mode history of one accumulator set (caller holds L->mu).  A new set gets a fresh
+// entry; when the table is full the least recently used entry is dropped first, so the table
+// cannot grow without bound if a caller never resets.  Returns nullptr if the host is out of memory.
+odc_layout::History *history_of(odc_layout_t *L, const void *key, bool *inserted)
+{
+    *inserted = false;
+    auto it = L->last.find(key);
+    if (it == L->last.end()) {
+        if (L->last.size() >= odc_layout::kMaxHistory) {
+            auto oldest = L->last.begin();
+            for (auto j = L->last.begin(); j != L->last.end(); ++j)
+                if (j->second.used < oldest->second.used) oldest = j;
+            L->last.erase(oldest);
+        }
+        try {
+            it = L->last.emplace(key, odc_layout::History{}).first;
+        } catch (...) {
+            return nullptr;
+        }
+        *inserted = true;
+    }
+    it->second.used = ++L->clock;
+    return &it->second;
 }
 
 int upload_table(odc_layout_t *L)
@@ -206,13 +238,9 @@ static int scatter_accumulate_impl(const odc_layout_t *L, const void *grad_full,
     bool inserted = false;
     if (!atomic) {
         lock.lock();
-        try {
-            auto res = M->last.try_emplace(accum_shards[0], -1, -1);
-            slot = &res.first->second;
-            inserted = res.second;
-        } catch (...) {
-            return ODC_ERR_NOMEM;
-        }
+        odc_layout::History *h = history_of(M, accum_shards[0], &inserted);
+        if (!h) return ODC_ERR_NOMEM;
+        slot = &h->last;
         if (!(*slot < now)) return ODC_ERR_ORDER;
     }
     rc = check_device(L);
@@ -279,13 +307,9 @@ int odc_scatter_accumulate_multi(const odc_layout_t *L, int count, const void *c
             if (!(a < b)) return ODC_ERR_ORDER;
         }
         lock.lock();
-        try {
-            auto res = M->last.try_emplace(accum_shards[0], -1, -1);
-            slot = &res.first->second;
-            inserted = res.second;
-        } catch (...) {
-            return ODC_ERR_NOMEM;
-        }
+        odc_layout::History *h = history_of(M, accum_shards[0], &inserted);
+        if (!h) return ODC_ERR_NOMEM;
+        slot = &h->last;
         if (!(*slot < std::pair<int, int>{workers[0], microbatches[0]})) {
             if (inserted) M->last.erase(accum_shards[0]);
             return ODC_ERR_ORDER;
@@ -522,6 +546,10 @@ int odc_reset_accum(const odc_layout_t *L, void *const *accum_shards, void *stre
     rc = check_device(L);
     if (rc != ODC_OK) return rc;
     const odc::HostLayout &H = L->host;
+    odc_layout_t *M = const_cast<odc_layout_t *>(L);
+    // the lock covers the launch and the erase, so that history and stream order agree when
+    // several host threads work on one accumulator set
+    std::lock_guard<std::mutex> lock(M->mu);
     for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
         const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
         int e;
@@ -531,6 +559,13 @@ int odc_reset_accum(const odc_layout_t *L, void *const *accum_shards, void *stre
             e = odc::launch_reset_batched(L->table, accum_shards + r0, r0, nr, stream);
         if (e != 0) return hip_fail(static_cast<hipError_t>(e));
     }
+    M->last.erase(accum_shards[0]);
+    return ODC_OK;
+}
+
+int odc_forget_accum(const odc_layout_t *L, void *const *accum_shards)
+{
+    if (!L || !accum_shards || !accum_shards[0]) return ODC_ERR_INVALID_ARG;
     odc_layout_t *M = const_cast<odc_layout_t *>(L);
     std::lock_guard<std::mutex> lock(M->mu);
     M->last.erase(accum_shards[0]);
@@ -566,7 +601,11 @@ int odc_probe_copy(void *dst, const void *src, int64_t bytes, void *stream)
 int odc_tune(const char *knob, int value)
 {
     if (!knob) return ODC_ERR_INVALID_ARG;
-    odc::Tuning &t = odc::tuning();
+    // read-modify-write of the whole set under the API's own lock, so two tuning calls cannot
+    // lose each other's change
+    static std::mutex tune_mu;
+    std::lock_guard<std::mutex> tune_lock(tune_mu);
+    odc::Tuning t = odc::tuning();
     const bool unroll_ok = value == 1 || value == 2 || value == 4;
     const bool threads_ok = value == 64 || value == 128 || value == 256;
     const bool flag_ok = value == 0 || value == 1;
@@ -587,6 +626,7 @@ int odc_tune(const char *knob, int value)
              (value == 0 || value == 1 || value == 2 || value == 4 || value == 8))
         t.batch_rank_group = value;
     else return ODC_ERR_INVALID_ARG;
+    odc::set_tuning(t);
     return ODC_OK;
 }
 

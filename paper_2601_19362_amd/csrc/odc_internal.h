@@ -109,7 +109,11 @@ struct Tuning {
     int batch_rank_group = 0;  // owners per workgroup in batched accumulate/reset: 0 = auto, 1, 2, 4, 8
     int gather_tile_xcd_block = 8;  // batched gather: tiles handed to the 8 XCDs in blocks of this many (power of two)
 };
-Tuning &tuning();
+// The knobs are process-wide.  Every launcher takes ONE copy at its start (under a lock) and
+// computes grid, kernel variant and kernel arguments from that copy, so a thread that changes a
+// knob while another launches can never make a launch see half of a change.
+Tuning tuning();
+void set_tuning(const Tuning &t);
 
 // Kernel launchers (odc_kernels.hip).  All return a hipError_t as int.  `ptrs` holds the
 // device base pointers of ranks [r0, r0 + nr), nr <= kRanksPerLaunch.
@@ -172,6 +176,13 @@ struct odc_layout {
     void *d_blob = nullptr;  // one hipMalloc holding shard_off, desc and chunk_first
     odc::BatchTable table{};
     std::mutex mu;
-    // ordered-mode history: accum_shards[0] -> last (worker, microbatch)
-    std::unordered_map<const void *, std::pair<int, int>> last;
+    // ordered-mode history: accum_shards[0] -> last (worker, microbatch) issued, with the time of
+    // its last use; bounded (the least recently used entry goes when kMaxHistory is reached)
+    struct History {
+        std::pair<int, int> last{-1, -1};
+        uint64_t used = 0;
+    };
+    static constexpr size_t kMaxHistory = 1024;
+    std::unordered_map<const void *, History> last;
+    uint64_t clock = 0;
 };

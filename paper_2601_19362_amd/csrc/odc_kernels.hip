@@ -21,17 +21,16 @@ RankPtrs pack(const void *const *ptrs, int nr)
 
 // Grid for `items` work items at TPB * U items per tile.  With tile remapping the x extent
 // is rounded up to a multiple of 8 (one slot per XCD part) and never capped.
-dim3 grid_for(int64_t items, int per_block, int nr)
+dim3 grid_for(const Tuning &t, int64_t items, int per_block, int nr)
 {
-    const Tuning &t = tuning();
     unsigned gx = grid_x_for(items, per_block, t.tile_remap ? 0 : t.max_grid_x);
     if (t.tile_remap && gx <= 0x7FFFFFF0u) gx = (gx + 7u) & ~7u;
     return dim3(gx, static_cast<unsigned>(nr), 1);
 }
 
-dim3 plain_grid(int64_t items, int per_block, int nr)
+dim3 plain_grid(const Tuning &t, int64_t items, int per_block, int nr)
 {
-    return dim3(grid_x_for(items, per_block, tuning().max_grid_x), static_cast<unsigned>(nr), 1);
+    return dim3(grid_x_for(items, per_block, t.max_grid_x), static_cast<unsigned>(nr), 1);
 }
 
 int finish() { return static_cast<int>(hipGetLastError()); }
@@ -67,16 +66,16 @@ int finish() { return static_cast<int>(hipGetLastError()); }
 int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int64_t S, int64_t N,
                        void *stream)
 {
-    const Tuning &t = tuning();
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (t.gather_store_sc1 && t.nontemporal) {
         ODC_DISPATCH(t.gather_threads, t.gather_unroll, true,
-                     (k_gather_flat<TPB_, U_, NT_, true><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     (k_gather_flat<TPB_, U_, NT_, true><<<grid_for(t, (S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
                          rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
     } else {
         ODC_DISPATCH(t.gather_threads, t.gather_unroll, t.nontemporal != 0,
-                     (k_gather_flat<TPB_, U_, NT_, false><<<grid_for((S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     (k_gather_flat<TPB_, U_, NT_, false><<<grid_for(t, (S >> 3) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
                          rp, static_cast<uint16_t *>(full), S, N, r0, t.tile_remap)));
     }
     return finish();
@@ -85,13 +84,13 @@ int launch_gather_flat(const void *const *ptrs, int r0, int nr, void *full, int6
 int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64_t S, int64_t N,
                       bool atomic, bool weighted, float w, void *stream)
 {
-    const Tuning &t = tuning();
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
 #define ODC_ACCUM_FLAT(ATOMIC_, WEIGHTED_, NTF)                                                                 \
     ODC_DISPATCH(t.accum_threads, t.accum_unroll, NTF,                                                          \
-                 (k_accum_flat<TPB_, U_, NT_, ATOMIC_, WEIGHTED_><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>( \
+                 (k_accum_flat<TPB_, U_, NT_, ATOMIC_, WEIGHTED_><<<grid_for(t, (S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>( \
                      rp, g, S, N, r0, t.tile_remap, w)))
     if (atomic && weighted) ODC_ACCUM_FLAT(true, true, false);
     else if (atomic) ODC_ACCUM_FLAT(true, false, false);
@@ -103,20 +102,20 @@ int launch_accum_flat(void *const *ptrs, int r0, int nr, const void *grad, int64
 
 int launch_reset_flat(void *const *ptrs, int r0, int nr, int64_t S, int64_t N, void *stream)
 {
-    const Tuning &t = tuning();
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
-                 (k_reset_flat<TPB_, U_, NT_><<<grid_for((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                 (k_reset_flat<TPB_, U_, NT_><<<grid_for(t, (S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
                      rp, S, N, r0, t.tile_remap)));
     return finish();
 }
 
 // The batched kernels use fixed 256-thread workgroups: grid x = tiles (capped by the
 // max_grid_x knob, the kernels loop), y = owner groups for the arena-major kernels.
-static unsigned batched_grid_x(int64_t tiles)
+static unsigned batched_grid_x(const Tuning &t, int64_t tiles)
 {
-    return grid_x_for(tiles, 1, tuning().max_grid_x);
+    return grid_x_for(tiles, 1, t.max_grid_x);
 }
 
 // Owners per workgroup in the batched accumulate / reset / retrieve kernels.  A workgroup that
@@ -124,9 +123,9 @@ static unsigned batched_grid_x(int64_t tiles)
 // kernels on layouts of many small tensors when there is enough work to fill the chip; the
 // write-only reset, and layouts whose shard pieces are long (mean of 1024 elements or more:
 // most tiles then lie inside one tensor and take the lean path), are fastest with one.
-static int rank_group(const BatchTable &tb, int64_t tiles, int nr, int preferred)
+static int rank_group(const Tuning &t, const BatchTable &tb, int64_t tiles, int nr, int preferred)
 {
-    const int forced = tuning().batch_rank_group;
+    const int forced = t.batch_rank_group;
     if (forced > 0) return forced;
     if (tb.arena_elems / tb.T >= 1024) return 1;
     for (int rg = preferred; rg > 1; rg >>= 1)
@@ -147,17 +146,18 @@ static int rank_group(const BatchTable &tb, int64_t tiles, int nr, int preferred
 int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0, int nr, void *full,
                           void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint16_t *out = static_cast<uint16_t *>(full);
     const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
     int tshift = 0;
-    while ((1 << tshift) < tuning().gather_tile_xcd_block) ++tshift;
+    while ((1 << tshift) < t.gather_tile_xcd_block) ++tshift;
     const int64_t tgroup = int64_t{8} << tshift;
-    const dim3 grid(batched_grid_x((tiles + tgroup - 1) / tgroup * tgroup));
+    const dim3 grid(batched_grid_x(t, (tiles + tgroup - 1) / tgroup * tgroup));
 #define ODC_GATHER_BATCHED(CAP_, BIG_)                                 \
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,                         \
+    ODC_DISPATCH_NT(t.nontemporal != 0,                         \
                     (k_gather_batched<NT_, CAP_, BIG_><<<grid, kBatchThreads, 0, s>>>(tb, rp, out, r0, nr, tshift)))
     const bool few = tb.gather_tile_tensors <= kGatherFewTensors;
     if (few && tb.gather_big) ODC_GATHER_BATCHED(kGatherFewTensors, true);
@@ -171,32 +171,34 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
 int launch_accum_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *grad,
                          bool atomic, bool weighted, float w, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *g = static_cast<const uint16_t *>(grad);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tb, tiles, nr, 2);
-    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
+    const int rg = rank_group(t, tb, tiles, nr, 2);
+    const dim3 grid(batched_grid_x(t, tiles), static_cast<unsigned>((nr + rg - 1) / rg));
 #define ODC_ACCUM_BATCHED(ATOMIC_, WEIGHTED_, NTF)                                                     \
     ODC_DISPATCH_RG(rg, NTF,                                                                           \
                     (k_accum_batched<RG_, NT_, ATOMIC_, WEIGHTED_><<<grid, kBatchThreads, 0, s>>>(tb, rp, g, r0, nr, \
                                                                                                   w)))
     if (atomic && weighted) ODC_ACCUM_BATCHED(true, true, false);
     else if (atomic) ODC_ACCUM_BATCHED(true, false, false);
-    else if (weighted) ODC_ACCUM_BATCHED(false, true, tuning().nontemporal != 0);
-    else ODC_ACCUM_BATCHED(false, false, tuning().nontemporal != 0);
+    else if (weighted) ODC_ACCUM_BATCHED(false, true, t.nontemporal != 0);
+    else ODC_ACCUM_BATCHED(false, false, t.nontemporal != 0);
 #undef ODC_ACCUM_BATCHED
     return finish();
 }
 
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tb, tiles, nr, 1);
-    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
-    ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+    const int rg = rank_group(t, tb, tiles, nr, 1);
+    const dim3 grid(batched_grid_x(t, tiles), static_cast<unsigned>((nr + rg - 1) / rg));
+    ODC_DISPATCH_RG(rg, t.nontemporal != 0,
                     (k_reset_batched<RG_, NT_><<<grid, kBatchThreads, 0, s>>>(tb, rp, r0, nr)));
     return finish();
 }
@@ -224,10 +226,11 @@ static GradPtrs pack_grads(const void *const *grads, int count)
 int launch_accum_multi_flat(void *const *ptrs, int r0, int nr, const void *const *grads, int count, int64_t S,
                             int64_t N, bool atomic, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     const GradPtrs gp = pack_grads(grads, count);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid = plain_grid((S >> 2) + 1, 64, nr);
+    const dim3 grid = plain_grid(t, (S >> 2) + 1, 64, nr);
     if (atomic) ODC_DISPATCH_K(count, (k_accum_multi_flat<K_, true><<<grid, 64, 0, s>>>(rp, gp, S, N, r0)));
     else ODC_DISPATCH_K(count, (k_accum_multi_flat<K_, false><<<grid, 64, 0, s>>>(rp, gp, S, N, r0)));
     return finish();
@@ -236,10 +239,11 @@ int launch_accum_multi_flat(void *const *ptrs, int r0, int nr, const void *const
 int launch_accum_multi_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, const void *const *grads,
                                int count, bool atomic, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(ptrs, nr);
     const GradPtrs gp = pack_grads(grads, count);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
+    const dim3 grid(batched_grid_x(t, (tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
     if (atomic)
         ODC_DISPATCH_K(count, (k_accum_multi_batched<K_, true><<<grid, kBatchThreads, 0, s>>>(tb, rp, gp, r0)));
     else
@@ -257,10 +261,11 @@ int launch_stage_zero(void *flags, int64_t count, void *stream)
 int launch_stage_push_flat(void *const *staging, int r0, int nr, const void *grad, const void *flags, int64_t S,
                            int64_t N, int64_t slot, int R, int worker, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                    (k_stage_push_flat<NT_><<<plain_grid((S >> 3) + 1, 64, nr), 64, 0, s>>>(
+    ODC_DISPATCH_NT(t.nontemporal != 0,
+                    (k_stage_push_flat<NT_><<<plain_grid(t, (S >> 3) + 1, 64, nr), 64, 0, s>>>(
                         rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), S, N, slot, R,
                         r0, worker)));
     return finish();
@@ -269,11 +274,12 @@ int launch_stage_push_flat(void *const *staging, int r0, int nr, const void *gra
 int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0, int nr, const void *grad,
                               const void *flags, int64_t slot, int R, int worker, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs rp = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t chunks = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const dim3 grid(batched_grid_x((chunks + kPushChunks - 1) / kPushChunks), static_cast<unsigned>(nr));
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+    const dim3 grid(batched_grid_x(t, (chunks + kPushChunks - 1) / kPushChunks), static_cast<unsigned>(nr));
+    ODC_DISPATCH_NT(t.nontemporal != 0,
                     (k_stage_push_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,
                         worker)));
@@ -311,11 +317,12 @@ int launch_stage_clear(void *flags, const void *snapshot, int R, void *stream)
 int launch_stage_drain_flat(void *const *accs, const void *const *staging, int r0, int nr, const void *snapshot,
                             int64_t S, int64_t N, int64_t slot, int R, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs ra = pack(accs, nr);
     const RankPtrs rs = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,
-                    (k_stage_drain_flat<NT_><<<plain_grid((S >> 2) + 1, 64, nr), 64, 0, s>>>(
+    ODC_DISPATCH_NT(t.nontemporal != 0,
+                    (k_stage_drain_flat<NT_><<<plain_grid(t, (S >> 2) + 1, 64, nr), 64, 0, s>>>(
                         ra, rs, static_cast<const int32_t *>(snapshot), S, N, slot, R, r0)));
     return finish();
 }
@@ -323,11 +330,12 @@ int launch_stage_drain_flat(void *const *accs, const void *const *staging, int r
 int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const void *const *staging, int r0, int nr,
                                const void *snapshot, int64_t slot, int R, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs ra = pack(accs, nr);
     const RankPtrs rs = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(batched_grid_x((tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
-    ODC_DISPATCH_NT(tuning().nontemporal != 0,
+    const dim3 grid(batched_grid_x(t, (tb.arena_elems + kChunkElems - 1) >> kChunkShift), static_cast<unsigned>(nr));
+    ODC_DISPATCH_NT(t.nontemporal != 0,
                     (k_stage_drain_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
                         tb, ra, rs, static_cast<const int32_t *>(snapshot), slot, R, r0)));
     return finish();
@@ -336,17 +344,17 @@ int launch_stage_drain_batched(const BatchTable &tb, void *const *accs, const vo
 int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int nr, int64_t S, int64_t N,
                          float scale, bool bf16, void *stream)
 {
-    const Tuning &t = tuning();
+    const Tuning t = tuning();
     const RankPtrs ra = pack(acc, nr);
     const RankPtrs ro = pack(out, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (bf16) {
         ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
-                     (k_retrieve_flat<TPB_, U_, NT_, true><<<plain_grid((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     (k_retrieve_flat<TPB_, U_, NT_, true><<<plain_grid(t, (S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
                          ra, ro, S, N, r0, scale)));
     } else {
         ODC_DISPATCH(t.reset_threads, t.reset_unroll, t.nontemporal != 0,
-                     (k_retrieve_flat<TPB_, U_, NT_, false><<<plain_grid((S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
+                     (k_retrieve_flat<TPB_, U_, NT_, false><<<plain_grid(t, (S >> 2) + 1, TPB_ * U_, nr), TPB_, 0, s>>>(
                          ra, ro, S, N, r0, scale)));
     }
     return finish();
@@ -355,17 +363,18 @@ int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int n
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,
                             float scale, bool bf16, void *stream)
 {
+    const Tuning t = tuning();
     const RankPtrs ra = pack(acc, nr);
     const RankPtrs ro = pack(out, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t tiles = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const int rg = rank_group(tb, tiles, nr, 2);
-    const dim3 grid(batched_grid_x(tiles), static_cast<unsigned>((nr + rg - 1) / rg));
+    const int rg = rank_group(t, tb, tiles, nr, 2);
+    const dim3 grid(batched_grid_x(t, tiles), static_cast<unsigned>((nr + rg - 1) / rg));
     if (bf16) {
-        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+        ODC_DISPATCH_RG(rg, t.nontemporal != 0,
                         (k_retrieve_batched<RG_, NT_, true><<<grid, kBatchThreads, 0, s>>>(tb, ra, ro, r0, nr, scale)));
     } else {
-        ODC_DISPATCH_RG(rg, tuning().nontemporal != 0,
+        ODC_DISPATCH_RG(rg, t.nontemporal != 0,
                         (k_retrieve_batched<RG_, NT_, false><<<grid, kBatchThreads, 0, s>>>(tb, ra, ro, r0, nr, scale)));
     }
     return finish();
@@ -380,6 +389,7 @@ static_assert(kReduceSources == kReduceSourcesPerPass && kReduceRanks == kReduce
 int launch_reduce_groups(const BatchTable *tb, const void *const *srcs, int64_t stride, int count, bool init,
                          void *const *outs, int r0, int nr, int64_t S, int64_t N, void *stream)
 {
+    const Tuning t = tuning();
     ReducePtrs p{};
     for (int r = 0; r < kReduceRanks; ++r) {
         for (int k = 0; k < kReduceSources; ++k)
@@ -390,11 +400,11 @@ int launch_reduce_groups(const BatchTable *tb, const void *const *srcs, int64_t 
 #define ODC_REDUCE(K_, INIT_)                                                                                  \
     do {                                                                                                       \
         if (tb) {                                                                                              \
-            const dim3 grid(batched_grid_x((tb->arena_elems + kChunkElems - 1) >> kChunkShift),                 \
+            const dim3 grid(batched_grid_x(t, (tb->arena_elems + kChunkElems - 1) >> kChunkShift),                 \
                             static_cast<unsigned>(nr));                                                        \
             k_reduce_batched<K_, INIT_><<<grid, kBatchThreads, 0, s>>>(*tb, p, r0);                              \
         } else {                                                                                               \
-            k_reduce_flat<K_, INIT_><<<plain_grid((S >> 2) + 1, 64, nr), 64, 0, s>>>(p, S, N, r0);               \
+            k_reduce_flat<K_, INIT_><<<plain_grid(t, (S >> 2) + 1, 64, nr), 64, 0, s>>>(p, S, N, r0);               \
         }                                                                                                      \
     } while (0)
 #define ODC_REDUCE_K(INIT_)                               \

@@ -10,6 +10,7 @@
 #include "../../include/odc.h"
 
 #include <limits>
+#include <mutex>
 
 namespace odc {
 
@@ -115,10 +116,21 @@ int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out)
     return ODC_OK;
 }
 
-Tuning &tuning()
+namespace {
+std::mutex g_tuning_mu;
+Tuning g_tuning;
+}  // namespace
+
+Tuning tuning()
 {
-    static Tuning t;
-    return t;
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    return g_tuning;
+}
+
+void set_tuning(const Tuning &t)
+{
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    g_tuning = t;
 }
 
 }  // namespace odc

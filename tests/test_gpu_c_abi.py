@@ -27,7 +27,15 @@ def placement(numel, R):
 @pytest.mark.parametrize("numel,R", [([1_048_589], 4), ([4099, 1, 70_001, 12_345, 8, 300_000], 8), ([350, 9000], 70)])
 def test_c_program_through_the_c_abi(oracle, tmp_path, numel, R):
     if not os.path.exists(EXE):
-        pytest.skip("tests/c_abi/_build/c_abi_check is not built: run build() of __graft_entry__.py")
+        # build() makes it; a tree that lost it gets it rebuilt here (gcc, one second), and a
+        # failure to do so fails the test: a missing program must not pass as a skip
+        import sys
+
+        sys.path.insert(0, ROOT)
+        import __graft_entry__
+
+        __graft_entry__.build_c_abi_check()
+    assert os.path.exists(EXE), "tests/c_abi/_build/c_abi_check could not be built"
     print(f"c abi case R={R} numel={numel}", flush=True)
     p = subprocess.run([EXE, str(tmp_path), str(R)] + [str(n) for n in numel], capture_output=True, text=True,
                        timeout=100)

@@ -173,6 +173,29 @@ def test_ordered_mode_history_and_reset(oracle):
     case.close()
 
 
+def test_ordered_history_is_bounded_and_can_be_forgotten():
+    """The ordered-mode table keeps at most 1024 accumulator sets per layout (least recently used
+    out first), and odc_forget_accum drops one set's history without touching the accumulators."""
+    R, N = 2, 64
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    g = torch.zeros(N, dtype=torch.bfloat16, device="cuda")
+    pool = torch.zeros(1100 * R * S, dtype=torch.float32, device="cuda")
+    sets = [[pool[(2 * k + r) * S:(2 * k + r + 1) * S] for r in range(R)] for k in range(1100)]
+    sa = lambda k, w, m: odc.scatter_accumulate_rc(L, g, sets[k], w, m)
+    assert sa(0, 1, 5) == 0
+    assert sa(0, 1, 5) == odc.ODC_ERR_ORDER            # remembered
+    L.forget_accum(sets[0])
+    assert sa(0, 0, 0) == 0                             # forgotten: any (worker, microbatch) is fine again
+    assert sa(1, 1, 0) == 0
+    for k in range(2, 1100):                            # 1098 more sets: sets 0 and 1 are the oldest and go
+        assert sa(k, 1, 0) == 0
+    assert sa(1099, 1, 0) == odc.ODC_ERR_ORDER         # a recent set is still remembered
+    assert sa(0, 0, 0) == 0                             # the oldest was dropped and starts afresh
+    torch.cuda.synchronize()
+    L.close()
+
+
 def test_unordered_mode_within_tolerance(oracle):
     """Unordered mode: |x - ref64| <= 1e-6 * sum|g| per element against a float64 sum, with
     contributions issued in a scrambled order from two streams."""

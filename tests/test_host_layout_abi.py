@@ -184,3 +184,46 @@ def test_headers_compile_as_plain_c_and_cxx(tmp_path):
     if shutil.which("g++"):
         subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
                         "-x", "c++", str(src)], check=True)
+
+
+def test_forget_accum_is_host_only_and_checks_its_arguments():
+    L = odc.Layout(4, [1000], host_only=True)
+    import ctypes
+    fake = (ctypes.c_void_p * 4)(0x1000, 0x2000, 0x3000, 0x4000)      # never dereferenced
+    assert odc.lib().odc_forget_accum(L.handle, fake) == odc.ODC_OK     # no history: still fine
+    assert odc.lib().odc_forget_accum(L.handle, None) == odc.ODC_ERR_INVALID_ARG
+    assert odc.lib().odc_forget_accum(None, fake) == odc.ODC_ERR_INVALID_ARG
+    empty = (ctypes.c_void_p * 4)()
+    assert odc.lib().odc_forget_accum(L.handle, empty) == odc.ODC_ERR_INVALID_ARG
+    L.close()
+
+
+def test_tune_from_several_threads_keeps_every_knob_valid():
+    """odc_tune is a read-modify-write of the whole knob set under a lock: calls racing from
+    several threads must all be applied or refused cleanly, never tear the set.  Afterwards each
+    knob holds one of the values some thread wrote, and "defaults" restores the built-in set."""
+    import threading
+
+    knobs = {"gather_threads": (64, 128, 256), "accum_unroll": (1, 2, 4), "nontemporal": (0, 1),
+             "gather_tile_xcd_block": (1, 8, 64), "batch_rank_group": (0, 2, 8), "max_grid_x": (0, 7)}
+    errors = []
+
+    def worker(seed):
+        rng = np.random.default_rng(seed)
+        names = list(knobs)
+        for _ in range(3000):
+            k = names[rng.integers(len(names))]
+            v = knobs[k][rng.integers(len(knobs[k]))]
+            if odc.lib().odc_tune(k.encode(), int(v)) != odc.ODC_OK:
+                errors.append((k, v))
+            if odc.lib().odc_tune(b"gather_threads", 100) != odc.ODC_ERR_INVALID_ARG:     # refused, changes nothing
+                errors.append("bad value accepted")
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in range(6)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    odc.reset_tuning()
+    assert odc.lib().odc_tune(b"no_such_knob", 1) == odc.ODC_ERR_INVALID_ARG
