@@ -53,6 +53,75 @@ def test_kk_three_way_worked_example():
     assert sorted(map(sorted, parts)) == [[0], [1, 4], [2, 3]]
 
 
+def test_kk_equal_size_worked_example():
+    """equal_size with n = 6, k = 3, worked by hand.  Costs 9, 8, 7, 4, 3, 1 sorted descending are
+    grouped three at a time into tuples of singletons: A = (9, 8, 7), spread 2, and B = (4, 3, 1),
+    spread 3.  The larger spread is taken first, so B's i-th largest subset meets A's i-th
+    smallest: 4 + 7, 3 + 8, 1 + 9 = (11, 11, 10): parts {2, 3}, {1, 4}, {0, 5}, two items each.
+    The same with k = 2: pairs (10, 9), (7, 6), (3, 1) with spreads 1, 1, 2.  (3, 1) goes first
+    and meets the earlier of the two spread-1 pairs, (10, 9): 3 + 9, 1 + 10 = (12, 11); then (7, 6),
+    created before (12, 11), meets it: 7 + 11, 6 + 12 = (18, 18): parts {0, 2, 5} and {1, 3, 4}."""
+    for kk in (po.karmarkar_karp, packing.kk_partition):
+        costs = [9, 8, 7, 4, 3, 1]
+        parts = kk(costs, 3, True)
+        assert sums(costs, parts) == [11, 11, 10]
+        assert parts == [[1, 4], [2, 3], [0, 5]]          # equal sums: the part with the smaller first index first
+        costs = [10, 9, 7, 6, 3, 1]
+        parts = kk(costs, 2, True)
+        assert sums(costs, parts) == [18, 18]
+        assert parts == [[0, 2, 5], [1, 3, 4]]
+
+
+def test_kk_result_depends_on_the_stated_tie_break():
+    """Costs 5, 4, 3, 3, 2, 2, 2 into k = 3, by hand with the stated rules (larger spread first, among
+    equal spreads the tuple created earlier; subsets by sum, then by smallest index):
+      (5)+(4) -> (5, 4, 0) [spread 5];  it meets the earlier (3): (5, 4, 3) [2];
+      the other (3) meets the earliest (2): (3, 2, 0) [3];  it meets the next (2): (3, 2, 2) [1];
+      the last (2), created before (5, 4, 3), meets it: 2 + 3, 0 + 4, 0 + 5 = (5, 5, 4) [1];
+      (3, 2, 2), created before (5, 5, 4), meets it: 3 + 4, 2 + 5, 2 + 5 = (7, 7, 7).
+    Taking the LATER tuple among equal spreads instead ends in (8, 7, 6), so this instance tells
+    the two rules apart; both implementations must give the perfect split."""
+    costs = [5, 4, 3, 3, 2, 2, 2]
+    for kk in (po.karmarkar_karp, packing.kk_partition):
+        parts = kk(costs, 3, False)
+        assert sums(costs, parts) == [7, 7, 7]
+        assert parts == [[0, 5], [1, 3], [2, 4, 6]]
+
+
+def best_makespan_and_spread(costs, k):
+    """Exhaustive search over all k^n assignments: the smallest possible largest part and the
+    smallest possible spread (largest minus smallest part)."""
+    best_max, best_spread = None, None
+    for assign in itertools.product(range(k), repeat=len(costs)):
+        s = [0] * k
+        for c, a in zip(costs, assign):
+            s[a] += c
+        m, sp = max(s), max(s) - min(s)
+        best_max = m if best_max is None else min(best_max, m)
+        best_spread = sp if best_spread is None else min(best_spread, sp)
+    return best_max, best_spread
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_kk_against_exhaustive_search_on_small_inputs(seed):
+    """n <= 8 items, k in {2, 3, 4}: the differencing result can be no better than the optimum found
+    by exhaustive search, its spread is at most the largest item (merging largest with smallest
+    never widens a tuple beyond the wider of the two), and its largest part is within the factor
+    4/3 - 1/(3k) of the optimal one that is proven for the largest differencing method."""
+    rng = np.random.default_rng(100 + seed)
+    k = int(rng.choice([2, 3, 4]))
+    n = int(rng.integers(k + 1, 9))
+    costs = [int(v) for v in rng.integers(1, 60, size=n)]
+    opt_max, opt_spread = best_makespan_and_spread(costs, k)
+    for kk in (po.karmarkar_karp, packing.kk_partition):
+        parts = kk(costs, k, False)
+        assert_partition(parts, n, k)
+        s = sums(costs, parts)
+        assert max(s) >= opt_max and max(s) - min(s) >= opt_spread
+        assert max(s) - min(s) <= max(costs)
+        assert 3 * k * max(s) <= (4 * k - 1) * opt_max
+
+
 def scalar_differencing(costs):
     """Textbook two-way differencing on bare numbers: replace the two largest by their
     difference until one number is left.  Independent of the tuple-based oracle."""
