@@ -87,6 +87,13 @@ def _load():
             lib.odc_oracle_accumulate_weighted_batched.argtypes = [_vp, _vpp, _i64, _vp, _vp, _vp, _i64, _f32]
             lib.odc_oracle_retrieve_batched.restype = ctypes.c_int
             lib.odc_oracle_retrieve_batched.argtypes = [_vpp, _vpp, _i64, _vp, _vp, _i64, _f32, ctypes.c_int]
+            _f64pp = _vpp
+            lib.odc_oracle_accumulate_wide.restype = None
+            lib.odc_oracle_accumulate_wide.argtypes = [_vp, _f64pp, _i64, _i64, _i64, _i64]
+            lib.odc_oracle_reset_wide.restype = None
+            lib.odc_oracle_reset_wide.argtypes = [_f64pp, _i64, _i64, _i64, _i64]
+            lib.odc_oracle_retrieve_wide.restype = None
+            lib.odc_oracle_retrieve_wide.argtypes = [_f64pp, _vpp, _i64, _i64, ctypes.c_float, ctypes.c_int, _i64, _i64]
             lib.odc_oracle_reduce_groups.restype = None
             lib.odc_oracle_reduce_groups.argtypes = [_vpp, _i64, _vpp, _i64, _i64, _i64, _i64]
             lib.odc_oracle_reduce_groups_batched.restype = ctypes.c_int
@@ -245,6 +252,50 @@ def retrieve(acc, out, N: int, scale: float = 1.0, nthreads: int = 1, ranges=Non
     sc = float(np.float32(scale))
     fn = lib.odc_oracle_retrieve_bf16 if to_bf16 else lib.odc_oracle_retrieve_f32
     _run_ranges(lambda a, b: fn(pa, po, N, R, sc, a, b), N, nthreads, ranges)
+
+
+def accumulate_wide(g: np.ndarray, acc64, N: int, nthreads: int = 1, ranges=None) -> None:
+    """ONE contribution into binary64 accumulators: acc64_r[i] = fl64(acc64_r[i] + widen(g[r*S+i]))."""
+    R = len(acc64)
+    S = shard_elems(N, R)
+    _check(g, np.uint16, N, "g")
+    for r, a in enumerate(acc64):
+        _check(a, np.float64, S, f"acc64[{r}]")
+    lib = _load()
+    ptrs = _ptr_array(acc64)
+    _run_ranges(lambda a, b: lib.odc_oracle_accumulate_wide(g.ctypes.data, ptrs, N, R, a, b), N, nthreads, ranges)
+
+
+def reset_wide(acc64, N: int, nthreads: int = 1, ranges=None) -> None:
+    R = len(acc64)
+    S = shard_elems(N, R)
+    for r, a in enumerate(acc64):
+        _check(a, np.float64, S, f"acc64[{r}]")
+    lib = _load()
+    ptrs = _ptr_array(acc64)
+    _run_ranges(lambda a, b: lib.odc_oracle_reset_wide(ptrs, N, R, a, b), N, nthreads, ranges)
+
+
+def retrieve_wide(acc64, out, N: int, scale: float = 1.0, nthreads: int = 1, ranges=None) -> None:
+    """out_r[i] = cast(fl32(scale * fl32(acc64_r[i]))): one rounding to binary32, then as `retrieve`."""
+    R = len(acc64)
+    S = shard_elems(N, R)
+    to_bf16 = out[0].dtype == np.uint16
+    for r in range(R):
+        _check(acc64[r], np.float64, S, f"acc64[{r}]")
+        _check(out[r], np.uint16 if to_bf16 else np.float32, S, f"out[{r}]")
+    lib = _load()
+    pa, po = _ptr_array(acc64), _ptr_array(out)
+    sc = float(np.float32(scale))
+    _run_ranges(lambda a, b: lib.odc_oracle_retrieve_wide(pa, po, N, R, sc, 1 if to_bf16 else 0, a, b),
+                N, nthreads, ranges)
+
+
+def wide_views(arenas, numel, shard_off, t: int, R: int):
+    """Views of tensor t's shard slots inside R arenas (for the multi-tensor forms of the wide
+    routines, which handle one tensor after the other with the single-tensor routine)."""
+    S = -(-int(numel[t]) // R)
+    return [a[int(shard_off[t]):int(shard_off[t]) + S] for a in arenas]
 
 
 def reduce_groups(group_acc, out, N: int, nthreads: int = 1, ranges=None) -> None:

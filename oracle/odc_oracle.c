@@ -247,6 +247,63 @@ void odc_oracle_reduce_groups(const float *const *group_acc, int64_t K, float *c
 }
 
 /*
+ * Wide accumulators for the unordered mode.  When contributions are added in whatever order
+ * they arrive (Appendix B: the owner accumulates on receipt, several clients push at once), a
+ * binary32 accumulator can be off by up to (C - 1) * 2^-24 * sum|g| after C contributions, more
+ * than the 1e-6 tolerance of the unordered mode once C > 17.  Keeping the running sum in binary64
+ * removes the dependence on C and on the order: every addition of a widened bf16 value is
+ * rounded at 2^-53, and the sum is rounded to binary32 once, at retrieval (Section 3.2), so the
+ * retrieved gradient is within 2^-24 * (1 + C * 2^-29) of the exact sum relative to sum|g|.
+ *   accumulate_wide:  acc64_r[i] = fl64(acc64_r[i] + widen(g[r*S + i]))      for valid i
+ *   reset_wide:       acc64_r[i] = +0.0
+ *   retrieve_wide:    out_r[i]   = cast(fl32(scale * fl32(acc64_r[i])))      (binary32 or bf16 out)
+ * The reading taken for the retrieval: one rounding to binary32 first, then the same multiply
+ * and cast as the binary32 retrieval, so that both retrievals treat a value alike.
+ */
+void odc_oracle_accumulate_wide(const uint16_t *g, double *const *acc, int64_t N, int64_t R,
+                                int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i)
+            acc[r][i] = acc[r][i] + (double)widen_bf16(g[r * S + i]);
+    }
+}
+
+void odc_oracle_reset_wide(double *const *acc, int64_t N, int64_t R, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i)
+            acc[r][i] = 0.0;
+    }
+}
+
+/* out_is_bf16 = 0: out holds binary32; 1: bf16 bit patterns. */
+void odc_oracle_retrieve_wide(const double *const *acc, void *const *out, int64_t N, int64_t R,
+                              float scale, int out_is_bf16, int64_t j_begin, int64_t j_end)
+{
+    int64_t S = odc_oracle_shard_elems(N, R);
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t valid = odc_oracle_valid_elems(N, R, r);
+        int64_t i0 = lo_clip(j_begin, r * S);
+        int64_t i1 = hi_clip(j_end, r * S, valid);
+        for (int64_t i = i0; i < i1; ++i) {
+            float narrow = (float)acc[r][i];
+            float v = scale * narrow;
+            if (out_is_bf16) ((uint16_t *)out[r])[i] = narrow_to_bf16(v);
+            else ((float *)out[r])[i] = v;
+        }
+    }
+}
+
+/*
  * Batched forms (the many-small-tensor workload): T flat parameters, each
  * partitioned on its own by the rule above.  Where tensor t sits inside an
  * owner's buffer (shard_off[t], in elements, the same for every owner) and
