@@ -314,6 +314,9 @@ def main():
     rst_med, rst_min = time_kernel(lambda: L.reset_accum(s0[1]), torch)
     wac_med, wac_min = time_kernel(lambda: _accum_once(L, pool[1], s0[1], odc, weight=0.37), torch)
     una_med, una_min = time_kernel(lambda: L.scatter_accumulate(pool[0], s0[1], 0, 0, odc.ODC_UNORDERED), torch, reps=10)
+    acc64 = [torch.zeros(L.rank_arena_elems(), dtype=torch.float64, device="cuda") for _ in range(w.R)]
+    wid_med, wid_min = time_kernel(lambda: L.scatter_accumulate_wide(pool[0], acc64), torch, reps=10)
+    del acc64
     fused = {}
     for K in (2, 4, 8):
         if K <= len(pool):
@@ -367,6 +370,7 @@ def main():
             "reset_GBs": {"median": round(4 * total / rst_med / 1e6, 1), "best": round(4 * total / rst_min / 1e6, 1)},
             "scatter_accumulate_weighted_GBs": {"median": round(10 * total / wac_med / 1e6, 1), "best": round(10 * total / wac_min / 1e6, 1)},
             "scatter_accumulate_unordered_GBs (float atomics, 10 B rule)": {"median": round(10 * total / una_med / 1e6, 1), "best": round(10 * total / una_min / 1e6, 1)},
+            "scatter_accumulate_wide_GBs (binary64 atomics, 10 B rule)": {"median": round(10 * total / wid_med / 1e6, 1), "best": round(10 * total / wid_min / 1e6, 1)},
             "scatter_accumulate_fused (K contributions per pass, (2K+8) B/elem actual)": fused,
             "retrieve_f32_GBs": {"median": round(8 * total / r32_med / 1e6, 1), "best": round(8 * total / r32_min / 1e6, 1)},
             "retrieve_bf16_GBs": {"median": round(6 * total / r16_med / 1e6, 1), "best": round(6 * total / r16_min / 1e6, 1)},

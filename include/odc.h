@@ -264,6 +264,33 @@ int odc_retrieve_grads(const odc_layout_t *layout, const void *const *accum_shar
                        void *const *out_shards, float scale, int out_dtype, void *stream);
 
 /*
+ * Unordered accumulation with a guaranteed error: wide accumulators.  Contributions arrive in any
+ * order (Appendix B: the owner accumulates on receipt while several clients push).  A binary32
+ * accumulator updated one contribution at a time can be off by up to (C - 1) * 2^-24 * sum|g|
+ * after C contributions whatever the order, which exceeds 1e-6 * sum|g| for C > 17 on inputs
+ * built for it.  These calls keep the running sum in binary64 shards instead and round it to
+ * binary32 once, at retrieval: the retrieved gradient is within 2^-24 * (1 + C * 2^-29) * sum|g|
+ * (6e-8) of the exact sum for any inputs, any order, any number of streams.
+ *   accum64_shards  [R] host array of device pointers, IEEE binary64, >= odc_rank_arena_elems
+ *                   elements each (same element offsets as the binary32 accumulators), 16-byte aligned
+ * odc_reset_accum_wide          every valid element becomes +0.0.  8 bytes per valid element.
+ * odc_scatter_accumulate_wide   acc64[r][...] += widen(grad_full[...]) with one device-scope binary64
+ *                               atomic add per valid element; no order, no history, safe from
+ *                               several streams at once.  The atomics run at the memory side like the
+ *                               binary32 ones of ODC_UNORDERED, at about half their element rate.
+ * odc_retrieve_grads_wide       out_shards[r][...] = cast(fl32(scale * fl32(acc64[r][...]))): one
+ *                               rounding to binary32, then the multiply and cast of
+ *                               odc_retrieve_grads (out_dtype as there).  The accumulators are not
+ *                               modified.  12 or 10 bytes per valid element.
+ * Padding is never written.  All three enqueue one kernel per group of up to 64 ranks and return.
+ */
+int odc_reset_accum_wide(const odc_layout_t *layout, void *const *accum64_shards, void *stream);
+int odc_scatter_accumulate_wide(const odc_layout_t *layout, const void *grad_full, void *const *accum64_shards,
+                                void *stream);
+int odc_retrieve_grads_wide(const odc_layout_t *layout, const void *const *accum64_shards, void *const *out_shards,
+                            float scale, int out_dtype, void *stream);
+
+/*
  * Hybrid sharding (Section 6.1, Appendix E).  Parameters and gradients are sharded only inside
  * a group of R devices (a node); the world is `groups` such groups, world rank w belongs to
  * group w / R with local rank w % R.  Every group holds a full copy of the parameter shards

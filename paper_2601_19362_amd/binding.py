@@ -37,7 +37,8 @@ EXPORTS = (
     "odc_shard_offset", "odc_full_offset", "odc_gather", "odc_scatter_accumulate",
     "odc_reset_accum", "odc_forget_accum", "odc_scatter_accumulate_weighted", "odc_scatter_accumulate_multi", "odc_retrieve_grads",
     "odc_stage_slot_elems", "odc_stage_flag_count", "odc_stage_snapshot_count", "odc_stage_init",
-    "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_hybrid_group_of",
+    "odc_stage_push", "odc_stage_drain", "odc_stage_drain_noalloc", "odc_reset_accum_wide",
+    "odc_scatter_accumulate_wide", "odc_retrieve_grads_wide", "odc_hybrid_group_of",
     "odc_gather_hybrid", "odc_scatter_accumulate_hybrid", "odc_reduce_groups", "odc_strerror", "odc_last_hip_error", "odc_probe_copy", "odc_tune",
 )
 
@@ -106,6 +107,12 @@ def lib():
         L.odc_stage_drain.argtypes = [_vp, ctypes.POINTER(_vp), _vp, _vp, ctypes.POINTER(_vp), _vp]
         L.odc_stage_drain_noalloc.restype = _int
         L.odc_stage_drain_noalloc.argtypes = [_vp, ctypes.POINTER(_vp), _vp, ctypes.POINTER(_vp), _vp]
+        L.odc_reset_accum_wide.restype = _int
+        L.odc_reset_accum_wide.argtypes = [_vp, ctypes.POINTER(_vp), _vp]
+        L.odc_scatter_accumulate_wide.restype = _int
+        L.odc_scatter_accumulate_wide.argtypes = [_vp, _vp, ctypes.POINTER(_vp), _vp]
+        L.odc_retrieve_grads_wide.restype = _int
+        L.odc_retrieve_grads_wide.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.c_float, _int, _vp]
         L.odc_hybrid_group_of.restype = _int
         L.odc_hybrid_group_of.argtypes = [_vp, _int, _int]
         L.odc_gather_hybrid.restype = _int
@@ -290,6 +297,25 @@ class Layout:
         rc = stage_drain_noalloc_rc(self, staging_shards, flags, accum_shards, stream)
         if rc != ODC_OK:
             raise OdcError(rc, "odc_stage_drain_noalloc")
+
+    # -- wide (binary64) accumulators of the unordered mode
+    def reset_accum_wide(self, accum64_shards, stream=None) -> None:
+        rc = lib().odc_reset_accum_wide(self._h, _ptr_array(accum64_shards, self.R), _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_reset_accum_wide")
+
+    def scatter_accumulate_wide(self, grad_full, accum64_shards, stream=None) -> None:
+        rc = lib().odc_scatter_accumulate_wide(self._h, _ptr(grad_full), _ptr_array(accum64_shards, self.R),
+                                               _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_scatter_accumulate_wide")
+
+    def retrieve_grads_wide(self, accum64_shards, out_shards, scale: float = 1.0, out_dtype: int = ODC_OUT_F32,
+                            stream=None) -> None:
+        rc = lib().odc_retrieve_grads_wide(self._h, _ptr_array(accum64_shards, self.R), _ptr_array(out_shards, self.R),
+                                           float(scale), int(out_dtype), _stream(stream))
+        if rc != ODC_OK:
+            raise OdcError(rc, "odc_retrieve_grads_wide")
 
     # -- hybrid sharding: group-major lists of groups * R buffers
     def hybrid_group_of(self, groups: int, world_worker: int) -> int:

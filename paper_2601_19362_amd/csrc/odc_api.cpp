@@ -476,6 +476,50 @@ int odc_retrieve_grads(const odc_layout_t *L, const void *const *accum_shards, v
     return ODC_OK;
 }
 
+// ---------------------------------------------------------------------- wide accumulators
+static int wide_call(const odc_layout_t *L, int op, void *const *accum64_shards, void *const *out_shards,
+                     const void *grad_full, float scale, void *stream)
+{
+    int rc = check_launchable(L, accum64_shards);
+    if (rc != ODC_OK) return rc;
+    if (out_shards) {
+        rc = check_launchable(L, out_shards);
+        if (rc != ODC_OK) return rc;
+    }
+    rc = check_device(L);
+    if (rc != ODC_OK) return rc;
+    const odc::HostLayout &H = L->host;
+    const odc::BatchTable *tb = H.T == 1 ? nullptr : &L->table;
+    for (int r0 = 0; r0 < H.R; r0 += odc::kRanksPerLaunch) {
+        const int nr = H.R - r0 < odc::kRanksPerLaunch ? H.R - r0 : odc::kRanksPerLaunch;
+        const int e = odc::launch_wide(tb, op, accum64_shards + r0, out_shards ? out_shards + r0 : nullptr, grad_full, r0,
+                                       nr, H.desc[0].S, H.desc[0].numel, scale, stream);
+        if (e != 0) return hip_fail(static_cast<hipError_t>(e));
+    }
+    return ODC_OK;
+}
+
+int odc_scatter_accumulate_wide(const odc_layout_t *L, const void *grad_full, void *const *accum64_shards, void *stream)
+{
+    if (!grad_full) return ODC_ERR_INVALID_ARG;
+    if (!aligned16(grad_full)) return ODC_ERR_ALIGNMENT;
+    return wide_call(L, 0, accum64_shards, nullptr, grad_full, 1.0f, stream);
+}
+
+int odc_reset_accum_wide(const odc_layout_t *L, void *const *accum64_shards, void *stream)
+{
+    return wide_call(L, 1, accum64_shards, nullptr, nullptr, 1.0f, stream);
+}
+
+int odc_retrieve_grads_wide(const odc_layout_t *L, const void *const *accum64_shards, void *const *out_shards, float scale,
+                            int out_dtype, void *stream)
+{
+    if (out_dtype != ODC_OUT_F32 && out_dtype != ODC_OUT_BF16) return ODC_ERR_INVALID_ARG;
+    if (!out_shards) return ODC_ERR_INVALID_ARG;
+    return wide_call(L, out_dtype == ODC_OUT_BF16 ? 3 : 2, const_cast<void *const *>(accum64_shards), out_shards, nullptr,
+                     scale, stream);
+}
+
 // ------------------------------------------------------------------------ hybrid sharding
 int odc_hybrid_group_of(const odc_layout_t *L, int groups, int world_worker)
 {

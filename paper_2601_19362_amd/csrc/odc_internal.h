@@ -159,6 +159,10 @@ int launch_retrieve_flat(const void *const *acc, void *const *out, int r0, int n
 int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *const *out, int r0, int nr,
                             float scale, bool bf16, void *stream);
 int launch_reset_batched(const BatchTable &tb, void *const *ptrs, int r0, int nr, void *stream);
+// Wide (binary64) accumulators of the unordered mode: op 0 accumulate (atomic), 1 reset,
+// 2 retrieve to binary32, 3 retrieve to bf16; tb = nullptr: single tensor with S, N.
+int launch_wide(const BatchTable *tb, int op, void *const *accs, void *const *outs, const void *grad, int r0, int nr,
+                int64_t S, int64_t N, float scale, void *stream);
 // Hybrid sharding: one pass of the sum over groups (tb = nullptr: single tensor with S, N).
 constexpr int kReduceSourcesPerPass = 8;
 constexpr int kReduceRanksPerLaunch = 16;

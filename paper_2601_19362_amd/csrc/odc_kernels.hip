@@ -380,6 +380,37 @@ int launch_retrieve_batched(const BatchTable &tb, const void *const *acc, void *
     return finish();
 }
 
+// Wide (binary64) accumulators: op 0 accumulate, 1 reset, 2 retrieve to binary32, 3 retrieve to bf16.
+int launch_wide(const BatchTable *tb, int op, void *const *accs, void *const *outs, const void *grad, int r0, int nr,
+                int64_t S, int64_t N, float scale, void *stream)
+{
+    const Tuning t = tuning();
+    const RankPtrs ra = pack(accs, nr);
+    RankPtrs ro{};
+    if (outs) ro = pack(outs, nr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint16_t *g = static_cast<const uint16_t *>(grad);
+#define ODC_WIDE(OP_)                                                                                         \
+    do {                                                                                                      \
+        if (tb) {                                                                                             \
+            const dim3 grid(batched_grid_x(t, (tb->arena_elems + kChunkElems - 1) >> kChunkShift),             \
+                            static_cast<unsigned>(nr));                                                       \
+            k_wide_batched<OP_><<<grid, kBatchThreads, 0, s>>>(*tb, ra, ro, g, r0, scale);                     \
+        } else {                                                                                              \
+            k_wide_flat<OP_><<<plain_grid(t, S + 1, kWideThreads * kWideElems, nr), kWideThreads, 0, s>>>(ra, ro, g, S, N, \
+                                                                                                         r0, scale); \
+        }                                                                                                     \
+    } while (0)
+    switch (op) {
+        case kWideAccumulate: ODC_WIDE(kWideAccumulate); break;
+        case kWideReset: ODC_WIDE(kWideReset); break;
+        case kWideRetrieveF32: ODC_WIDE(kWideRetrieveF32); break;
+        default: ODC_WIDE(kWideRetrieveBf16); break;
+    }
+#undef ODC_WIDE
+    return finish();
+}
+
 // One pass of the group reduction: owners [r0, r0 + nr), nr <= kReduceRanks; `count` sources per
 // owner (1..kReduceSources), srcs[k * stride + r] = source k of owner r0 + r; init: the sum starts
 // from the first source instead of the stored value of out.

@@ -14,6 +14,7 @@
 #include <cstdlib>
 #include <string>
 #include <thread>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/odc.h"
@@ -477,6 +478,67 @@ int main(int argc, char **argv)
         for (auto *b : stages) std::free(b);
         std::free(flags);
         std::free(snap);
+        return 0;
+    }
+
+    if (op == "wide") {
+        // acc.f64 [R * arena] in/out; grad<k>.u16 for k < count: reset, count contributions, then both
+        // retrievals into out32.f32 / out16.u16 [R * arena] (in/out)
+        std::vector<double> all = read_file<double>(dir + "/acc.f64");
+        std::vector<float> o32 = read_file<float>(dir + "/out32.f32");
+        std::vector<uint16_t> o16 = read_file<uint16_t>(dir + "/out16.u16");
+        if (all.size() != arena * static_cast<size_t>(R) || o32.size() != all.size() || o16.size() != all.size()) return 4;
+        std::vector<double *> accs(static_cast<size_t>(R));
+        std::vector<float *> out32(static_cast<size_t>(R));
+        std::vector<uint16_t *> out16(static_cast<size_t>(R));
+        for (int r = 0; r < R; ++r) {
+            accs[r] = static_cast<double *>(std::malloc(arena * 8));
+            std::memcpy(accs[r], all.data() + arena * r, arena * 8);
+            out32[r] = static_cast<float *>(std::malloc(arena * 4));
+            std::memcpy(out32[r], o32.data() + arena * r, arena * 4);
+            out16[r] = static_cast<uint16_t *>(std::malloc(arena * 2));
+            std::memcpy(out16[r], o16.data() + arena * r, arena * 2);
+        }
+        std::vector<uint16_t *> grads;
+        for (int k = 0; k < count; ++k) {
+            std::vector<uint16_t> gi = read_file<uint16_t>(dir + "/grad" + std::to_string(k) + ".u16");
+            if (gi.size() != full_n) return 4;
+            grads.push_back(static_cast<uint16_t *>(std::malloc(full_n * 2)));
+            std::memcpy(grads.back(), gi.data(), full_n * 2);
+        }
+        auto run_op = [&](auto op_tag, void *const *outs, const uint16_t *g) {
+            constexpr int OP = decltype(op_tag)::value;
+            for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
+                const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
+                RankPtrs ra{}, ro{};
+                for (int k = 0; k < nr; ++k) {
+                    ra.p[k] = accs[r0 + k];
+                    ro.p[k] = outs ? outs[r0 + k] : nullptr;
+                }
+                if (flat)
+                    run_grid(kWideThreads, grid_x_for(S + 1, kWideThreads * kWideElems, cap), nr,
+                             [&] { k_wide_flat<OP>(ra, ro, g, S, N, r0, scale); });
+                else
+                    run_grid_threaded(kBatchThreads, grid_x_for((tb.arena_elems + kChunkElems - 1) >> kChunkShift, 1, cap),
+                                      static_cast<unsigned>(nr), [&] { k_wide_batched<OP>(tb, ra, ro, g, r0, scale); });
+            }
+        };
+        run_op(std::integral_constant<int, kWideReset>{}, nullptr, nullptr);
+        for (auto *g : grads) run_op(std::integral_constant<int, kWideAccumulate>{}, nullptr, g);
+        run_op(std::integral_constant<int, kWideRetrieveF32>{}, reinterpret_cast<void *const *>(out32.data()), nullptr);
+        run_op(std::integral_constant<int, kWideRetrieveBf16>{}, reinterpret_cast<void *const *>(out16.data()), nullptr);
+        for (int r = 0; r < R; ++r) {
+            std::memcpy(all.data() + arena * r, accs[r], arena * 8);
+            std::memcpy(o32.data() + arena * r, out32[r], arena * 4);
+            std::memcpy(o16.data() + arena * r, out16[r], arena * 2);
+            std::free(accs[r]);
+            std::free(out32[r]);
+            std::free(out16[r]);
+        }
+        for (auto *g : grads) std::free(g);
+        write_file(dir + "/acc.out", all.data(), all.size());
+        write_file(dir + "/out32.out", o32.data(), o32.size());
+        write_file(dir + "/out16.out", o16.data(), o16.size());
         return 0;
     }
 

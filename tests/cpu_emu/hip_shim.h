@@ -39,6 +39,7 @@ static inline float __uint_as_float(uint32_t u)
 }
 
 static inline void unsafeAtomicAdd(float *a, float v) { *a = *a + v; }
+static inline void unsafeAtomicAdd(double *a, double v) { *a = *a + v; }
 
 static inline int atomicAdd(int32_t *p, int v)
 {

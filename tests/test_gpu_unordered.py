@@ -6,8 +6,10 @@ sum of the widened bf16 contributions built by the oracle (a forward-error form:
 max|x - ref64| / max|ref64| is printed beside it.  One float atomic per element and contribution
 is a sequential binary32 sum in arrival order, whose worst case over ALL inputs is
 (C - 1) * 2^-24 * sum|g|, above 1e-6 for C > 17; what is asserted here is the error on the
-configurations' own data (Normal gradients), where it stays far below the tolerance, and
-`test_compensated_*` covers inputs built to hit the worst case."""
+configurations' own data (Normal gradients), where it stays far below the tolerance.  The wide
+(binary64) accumulators in the second half of this file hold the tolerance for any inputs, and
+`test_wide_keeps_the_tolerance_where_binary32_atomics_cannot` runs an input built to hit the
+worst case through both."""
 import os
 
 import numpy as np
@@ -156,4 +158,157 @@ def test_unordered_at_stress_contribution_count(oracle):
         err_max, ref_max = max(err_max, float(err.max())), max(ref_max, float(np.abs(tot[fo[t]:fo[t] + n]).max()))
     print(f"unordered stress C={len(seq)}: worst |err| / sum|g| = {worst:.3e} (tolerance {TOL:.0e}); normwise "
           f"{err_max / ref_max:.3e}", flush=True)
+    L.close()
+
+
+# ----------------------------------------------------------------------------- wide accumulators
+def wide_case(oracle, numel, R, C, seed, streams=3):
+    """reset, C contributions in scrambled order on several streams, both retrievals; the binary64
+    sums of these inputs are exact (no rounding at this magnitude), so every order gives the same
+    bits and the GPU must equal the oracle bit for bit, accumulators and outputs."""
+    print(f"wide case R={R} T={len(numel)} total={sum(numel)} C={C}", flush=True)
+    L = odc.Layout(R, numel)
+    T = len(numel)
+    so = [L.shard_offset(t) for t in range(T)]
+    fo = [L.full_offset(t) for t in range(T)]
+    arena, full_n = L.rank_arena_elems(), L.full_elems()
+    dev = torch.device("cuda")
+    PAD = -9876.5
+    acc = [torch.full((arena,), PAD, dtype=torch.float64, device=dev) for _ in range(R)]
+    acc_h = [np.full(arena, PAD, dtype=np.float64) for _ in range(R)]
+    L.reset_accum_wide(acc)
+    gs = [inputs.normal_bf16(full_n, 1e-2, seed=(seed, k)) for k in range(C)]
+    dev_g = [torch.from_numpy(g.view(np.int16)).cuda() for g in gs]
+    torch.cuda.synchronize()
+    ss = [torch.cuda.Stream() for _ in range(streams)]
+    order = list(range(C))
+    np.random.default_rng(seed).shuffle(order)
+    for i, k in enumerate(order):
+        L.scatter_accumulate_wide(dev_g[k], acc, stream=ss[i % streams])
+    torch.cuda.synchronize()
+    out32 = [torch.full((arena,), 77.0, dtype=torch.float32, device=dev) for _ in range(R)]
+    out16 = [torch.full((arena,), 0x1234, dtype=torch.int16, device=dev) for _ in range(R)]
+    scale = 1.0 / C
+    L.retrieve_grads_wide(acc, out32, scale, odc.ODC_OUT_F32)
+    L.retrieve_grads_wide(acc, out16, scale, odc.ODC_OUT_BF16)
+    torch.cuda.synchronize()
+    o32_h = [np.full(arena, 77.0, dtype=np.float32) for _ in range(R)]
+    o16_h = [np.full(arena, 0x1234, dtype=np.uint16) for _ in range(R)]
+    for t, n in enumerate(numel):
+        va = oracle.wide_views(acc_h, numel, so, t, R)
+        oracle.reset_wide(va, n)
+        for g in gs:
+            oracle.accumulate_wide(np.ascontiguousarray(g[fo[t]:fo[t] + n]), va, n)
+        oracle.retrieve_wide(va, oracle.wide_views(o32_h, numel, so, t, R), n, scale=scale)
+        oracle.retrieve_wide(va, oracle.wide_views(o16_h, numel, so, t, R), n, scale=scale)
+    for r in range(R):
+        assert np.array_equal(acc[r].cpu().numpy().view(np.uint64), acc_h[r].view(np.uint64)), f"wide accumulator of owner {r}"
+        assert np.array_equal(out32[r].cpu().numpy().view(np.uint32), o32_h[r].view(np.uint32)), f"binary32 retrieval, owner {r}"
+        assert np.array_equal(out16[r].cpu().numpy().view(np.uint16), o16_h[r]), f"bf16 retrieval, owner {r}"
+    L.close()
+
+
+@pytest.mark.parametrize("numel,R,C", [([1_048_589], 4, 9), ([1], 64, 3), ([3_000_001], 16, 20), ([350], 70, 4),
+                                       ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8, 7),
+                                       ([30000, 17, 2048, 2049, 1_000_001], 5, 12), ([5] * 70 + [100_000], 70, 5)])
+def test_wide_accumulators_equal_the_oracle_in_any_order(oracle, numel, R, C):
+    wide_case(oracle, numel, R, C, seed=sum(numel) % 991 + C)
+
+
+def test_wide_accumulators_on_the_stress_config(oracle):
+    wl = inputs.workload("stress")
+    wide_case(oracle, list(wl.numel), wl.R, 6, seed=17)
+
+
+def test_wide_keeps_the_tolerance_where_binary32_atomics_cannot(oracle):
+    """An input built to hit the worst case of a binary32 running sum: 1.0 first, then 271
+    contributions of 2^-17 + 2^-24 (exact in bf16), all on one stream so that they arrive in that
+    order.  Every binary32 addition is a tie that rounds the 2^-24 away: the plain unordered mode
+    ends 1.6e-5 * sum|g| off, 16 times the tolerance, while the wide accumulators stay within
+    2^-24 * sum|g| after their single rounding at retrieval."""
+    N, R, C = 1_000_003, 8, 272
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    big = torch.full((N,), 1.0, dtype=torch.bfloat16, device=dev)
+    small = torch.full((N,), 2.0 ** -17 + 2.0 ** -24, dtype=torch.bfloat16, device=dev)
+    assert float(small[0]) == 2.0 ** -17 + 2.0 ** -24
+    exact = 1.0 + (C - 1) * (2.0 ** -17 + 2.0 ** -24)            # exact in binary64; all terms positive
+    acc32 = [torch.zeros(S, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc64 = [torch.zeros(S, dtype=torch.float64, device=dev) for _ in range(R)]
+    L.reset_accum(acc32)
+    L.reset_accum_wide(acc64)
+    for k in range(C):
+        g = big if k == 0 else small
+        L.scatter_accumulate(g, acc32, 0, 0, odc.ODC_UNORDERED)
+        L.scatter_accumulate_wide(g, acc64)
+    out = [torch.zeros(S, dtype=torch.float32, device=dev) for _ in range(R)]
+    L.retrieve_grads_wide(acc64, out, 1.0, odc.ODC_OUT_F32)
+    torch.cuda.synchronize()
+    worst32 = worst64 = 0.0
+    for r in range(R):
+        v = L.valid_elems(0, r)
+        worst32 = max(worst32, float((acc32[r][:v].double() - exact).abs().max()) / exact)
+        worst64 = max(worst64, float((out[r][:v].double() - exact).abs().max()) / exact)
+        assert bool((acc64[r][:v] == exact).all())
+    print(f"adversarial C={C}: binary32 atomics |err|/sum|g| = {worst32:.3e}; wide accumulators {worst64:.3e}", flush=True)
+    assert worst32 > 10 * TOL            # the sequence does what it was built for
+    assert worst64 <= 2.0 ** -24
+    L.close()
+
+
+def test_wide_at_the_7b_contribution_count(oracle):
+    """The 7B-shaped layer with all 37 contributions through the wide accumulators on three streams,
+    retrieved to binary32 and checked against the float64 reference at every element."""
+    wl = inputs.workload("7b")
+    N, R = wl.numel[0], wl.R
+    seq = contributions(inputs.microbatch_counts(wl))
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    acc = [torch.empty(S, dtype=torch.float64, device=dev) for _ in range(R)]
+    L.reset_accum_wide(acc)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    pinned = torch.empty(N, dtype=torch.int16, pin_memory=True)
+    g_h = pinned.numpy().view(np.uint16)
+    tot, mag = np.zeros(N), np.zeros(N)
+    pool = []
+    for k, (w, m) in enumerate(seq):
+        g = inputs.device_normal_bf16(N, wl.grad_sigma, 9900 + 64 * w + m, dev)
+        torch.cuda.current_stream().synchronize()
+        L.scatter_accumulate_wide(g, acc, stream=streams[k % 3])
+        pinned.copy_(g.view(torch.int16))
+        oracle.fp64_add(g_h, tot, mag, nthreads=THREADS)
+        pool.append(g)
+        if len(pool) > 6:
+            torch.cuda.synchronize()
+            pool.clear()
+    torch.cuda.synchronize()
+    out = [torch.zeros(S, dtype=torch.float32, device=dev) for _ in range(R)]
+    L.retrieve_grads_wide(acc, out, 1.0, odc.ODC_OUT_F32)
+    torch.cuda.synchronize()
+    worst = check_against_fp64(out, tot, mag, N, S, f"wide 7b C={len(seq)}")
+    assert worst <= 2.0 ** -24 * 1.01
+    L.close()
+
+
+def test_wide_argument_errors():
+    L = odc.Layout(4, [1000])
+    S = L.shard_elems(0)
+    acc = [torch.zeros(S, dtype=torch.float64, device="cuda") for _ in range(4)]
+    out = [torch.zeros(S, dtype=torch.float32, device="cuda") for _ in range(4)]
+    g = torch.zeros(1000, dtype=torch.bfloat16, device="cuda")
+    lib = odc.lib()
+    import ctypes
+    arr = lambda ts: (ctypes.c_void_p * 4)(*[t.data_ptr() for t in ts])
+    assert lib.odc_scatter_accumulate_wide(L.handle, None, arr(acc), None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_scatter_accumulate_wide(L.handle, g.data_ptr(), None, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_scatter_accumulate_wide(L.handle, g.data_ptr() + 2, arr(acc), None) == odc.ODC_ERR_ALIGNMENT
+    assert lib.odc_retrieve_grads_wide(L.handle, arr(acc), arr(out), ctypes.c_float(1.0), 9, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_retrieve_grads_wide(L.handle, arr(acc), None, ctypes.c_float(1.0), 0, None) == odc.ODC_ERR_INVALID_ARG
+    bad = [acc[0], acc[1][1:], acc[2], acc[3]]
+    assert lib.odc_reset_accum_wide(L.handle, arr(bad), None) == odc.ODC_ERR_ALIGNMENT
+    assert lib.odc_reset_accum_wide(L.handle, arr(acc), None) == 0
+    torch.cuda.synchronize()
     L.close()

@@ -307,6 +307,37 @@ def test_emulated_reduce_groups(oracle, emu, tmp_path, numel, R, K, inplace):
     assert np.array_equal(got.view(np.uint32), np.concatenate(want).view(np.uint32))
 
 
+@pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([1], 64), ([5] * 66, 66),
+                                     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5)])
+@pytest.mark.parametrize("count,cap", [(1, 0), (3, 2)])
+def test_emulated_wide_accumulators(oracle, emu, tmp_path, numel, R, count, cap):
+    """Binary64 accumulators: reset, contributions, retrieval to binary32 and to bf16; accumulators
+    and both outputs compared bit for bit with the oracle, sentinels in padding and gaps included."""
+    S, so, fo, arena, full_n = placement(numel, R)
+    np.array(numel, dtype=np.int64).tofile(tmp_path / "numel.i64")
+    acc = [np.full(arena, -9876.5, dtype=np.float64) for _ in range(R)]
+    out32 = [np.full(arena, PAD32, dtype=np.float32) for _ in range(R)]
+    out16 = [np.full(arena, PAD16, dtype=np.uint16) for _ in range(R)]
+    np.concatenate(acc).tofile(tmp_path / "acc.f64")
+    np.concatenate(out32).tofile(tmp_path / "out32.f32")
+    np.concatenate(out16).tofile(tmp_path / "out16.u16")
+    gs = [inputs.normal_bf16(full_n, 1e-2, seed=(23, k)) for k in range(count)]
+    for k, g in enumerate(gs):
+        g.tofile(tmp_path / f"grad{k}.u16")
+    scale = float(np.float32(1.0 / 3.0))
+    run(emu, tmp_path, "wide", R, count=count, cap=cap, scale=repr(scale))
+    for t, n in enumerate(numel):
+        va = oracle.wide_views(acc, numel, so, t, R)
+        oracle.reset_wide(va, n)
+        for g in gs:
+            oracle.accumulate_wide(np.ascontiguousarray(g[fo[t]:fo[t] + n]), va, n)
+        oracle.retrieve_wide(va, oracle.wide_views(out32, numel, so, t, R), n, scale=scale)
+        oracle.retrieve_wide(va, oracle.wide_views(out16, numel, so, t, R), n, scale=scale)
+    assert np.array_equal(np.fromfile(tmp_path / "acc.out", dtype=np.float64).view(np.uint64), np.concatenate(acc).view(np.uint64))
+    assert np.array_equal(np.fromfile(tmp_path / "out32.out", dtype=np.float32).view(np.uint32), np.concatenate(out32).view(np.uint32))
+    assert np.array_equal(np.fromfile(tmp_path / "out16.out", dtype=np.uint16), np.concatenate(out16))
+
+
 INTERLEAVINGS = [
     # a client pushes again while its slot is full; a drain on another stream empties the slot
     # after the claim / between the copy workgroups / before the raise
