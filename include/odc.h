@@ -32,8 +32,11 @@
  *     partly updated, and the contribution counts as issued.
  *   - Return value: ODC_OK (0) or a negative ODC_ERR_* code.  All argument errors are
  *     detected on the host before anything is enqueued.  Nothing throws or aborts.
- *   - Padding (shard slots whose flat index is >= numel) is never read into a result and
- *     never written, by any call.
+ *   - Padding (shard slots whose flat index is >= numel) and the alignment gaps between tensors
+ *     never reach a result and never change, by any call.  The read-modify-write calls
+ *     (scatter-accumulate, its fused form, the staging drain) may load such a slot together
+ *     with the valid slots of its 16-byte vector and store the very same bits back, so that
+ *     cache lines are written whole; every other call does not touch them at all.
  */
 #ifndef ODC_H
 #define ODC_H

@@ -782,33 +782,72 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
     }
 }
 
+// Valid elements of the 4-float vector at piece slot `slot`, and `gap`: the vector holds no valid
+// element but is the alignment gap behind a fully valid piece (slot below S rounded up to 8), so
+// that reading it and writing it back unchanged completes the piece's last cache line.
+__device__ __forceinline__ int vec_cover(const TensorDesc &d, int r, int64_t slot, bool &gap)
+{
+    int64_t valid = d.numel - static_cast<int64_t>(r) * d.S;
+    if (valid > d.S) valid = d.S;
+    const int64_t left = valid - slot;
+    gap = left <= 0 && valid == d.S && slot < ((d.S + 7) & ~int64_t{7});
+    return left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
+}
+
+// First `cnt` lanes from `fresh`, the others from `old`.
+__device__ __forceinline__ f32x4 keep_tail(f32x4 fresh, f32x4 old, int cnt)
+{
+    if (cnt < 1) fresh.x = old.x;
+    if (cnt < 2) fresh.y = old.y;
+    if (cnt < 3) fresh.z = old.z;
+    if (cnt < 4) fresh.w = old.w;
+    return fresh;
+}
+
 // One accumulate item: 4 floats at arena offset a of one owner, in two phases so that a
 // thread can issue the loads of all its items before it consumes any of them.
 struct AccumItem {
     u32x2 g;
     f32x4 acc;
-    int cnt;  // valid elements: 4 = whole vector, 1..3 = ragged end of a shard, 0 = nothing
+    int cnt;    // valid elements: 4 = whole vector, 1..3 = ragged end of a shard piece, 0 = none
+    bool wide;  // the accumulator vector was loaded whole and is stored whole
 };
 
-// A ragged item (1..3 valid elements at the end of a shard piece) still uses the two wide
-// loads -- the extra lanes read the next piece or alignment padding and are never stored --
-// unless that would run past the end of the arena or of the gradient buffer.  Keeping the
-// load phase uniform matters: nearly every wavefront of a many-small-tensor layout holds a
-// ragged item, and an element-wise load path would triple its memory instructions.
+// Every accumulator line is written whole.  A shard piece rarely ends on a cache-line boundary:
+// its last vector may hold only 1..3 valid elements, and up to 7 slots of alignment gap follow
+// before the next tensor's piece.  Storing just the valid elements leaves a hole in a line that
+// is otherwise rewritten completely, and the memory pays for a partly written line with a
+// read-modify-write of its own (a layout of 132-element pieces, no ragged vector but a 16-byte
+// hole per piece, ran 10 % slower than one of 136-element pieces).  So the slots after the valid
+// ones travel with the rest: a ragged vector is loaded whole and stored whole with the lanes
+// beyond `cnt` carrying the bits that were read, and the gap vector that completes a fully
+// valid piece's last line is read and written back unchanged.  No padding or gap value ever
+// changes.  The gradient load of a ragged vector is wide too (its extra lanes are the next
+// piece's elements and are thrown away).  Only where the 16 bytes would pass the end of the arena
+// or of the gradient buffer does an item go element by element.
 template <bool NT>
 __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc &d, int r, int64_t a,
                                                 float *__restrict__ arena, const uint16_t *__restrict__ grad,
                                                 int64_t arena_elems, int64_t full_elems)
 {
     const int64_t slot = a - d.shard_off;
-    it.cnt = valid_from(d, r, slot, 4);
+    bool gap;
+    it.cnt = vec_cover(d, r, slot, gap);
+    it.wide = false;
     const float *ap = arena + a;
-    if (it.cnt == 0) return;
+    if (it.cnt == 0) {
+        if (gap && a + 4 <= arena_elems) {
+            it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(ap));
+            it.wide = true;
+        }
+        return;
+    }
     const int64_t goff = d.full_off + static_cast<int64_t>(r) * d.S + slot;
     const uint16_t *gp = grad + goff;
     if (it.cnt == 4 || (a + 4 <= arena_elems && goff + 4 <= full_elems)) {
         it.g = ld_u64_unaligned<NT && kPieceLoadsNT>(gp);
         it.acc = ld<NT>(reinterpret_cast<const f32x4 *>(ap));
+        it.wide = true;
     } else {
         const uint32_t e0 = ld_u16(gp);
         const uint32_t e1 = it.cnt > 1 ? ld_u16(gp + 1) : 0u;
@@ -825,11 +864,12 @@ __device__ __forceinline__ void accum_item_load(AccumItem &it, const TensorDesc 
 template <bool NT, bool WEIGHTED>
 __device__ __forceinline__ void accum_item_store(const AccumItem &it, float *ap, float w)
 {
-    if (it.cnt == 0) return;
-    const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);  // lanes beyond cnt are computed but never stored
-    if (it.cnt == 4) {
-        st<NT>(reinterpret_cast<f32x4 *>(ap), sum);
-    } else {
+    if (it.wide) {
+        f32x4 out = it.acc;
+        if (it.cnt > 0) out = keep_tail(add4<WEIGHTED>(it.acc, it.g, w), it.acc, it.cnt);
+        st<NT>(reinterpret_cast<f32x4 *>(ap), out);
+    } else if (it.cnt > 0) {
+        const f32x4 sum = add4<WEIGHTED>(it.acc, it.g, w);
         st_f32(ap, sum.x);
         if (it.cnt > 1) st_f32(ap + 1, sum.y);
         if (it.cnt > 2) st_f32(ap + 2, sum.z);
@@ -943,6 +983,7 @@ __global__ __launch_bounds__(kBatchThreads) ODC_WAVES_PER_EU(RG == 2 ? 8 : 1) vo
                 for (int k = 0; k < RG; ++k) {
                     const int rl = rl0 + k;
                     items[u][k].cnt = 0;
+                    items[u][k].wide = false;
                     if (live && rl < nr)
                         accum_item_load<NT>(items[u][k], d, r0 + rl, a, static_cast<float *>(accs.p[rl]), grad,
                                             tb.arena_elems, tb.full_elems);
@@ -1019,27 +1060,26 @@ struct GradPtrs {
     const uint16_t *p[kMaxFused];
 };
 
-// One accumulator vector (ordered form); `cnt` < 4 marks a ragged item whose loads are still
-// wide (the caller has checked that they stay inside the buffers) and whose first cnt results
-// are kept.
+// One accumulator vector (ordered form), loaded whole and stored whole: lanes beyond `cnt` (the
+// ragged end of a shard piece, or cnt = 0: the alignment gap behind a piece) keep the bits that
+// were read.  The caller has checked that the wide loads stay inside the buffers.
 template <int K, bool NTG = true>
 __device__ __forceinline__ void accum_multi_vec(float *__restrict__ acc, const GradPtrs &grads, int64_t goff, int64_t q,
                                                 int cnt = 4)
 {
+    f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
+    if (cnt == 0) {
+        st<true>(av, ld<true>(av));
+        return;
+    }
     u32x2 gv[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) gv[k] = ld_u64_unaligned<NTG>(grads.p[k] + goff + 4 * q);
-    f32x4 *av = reinterpret_cast<f32x4 *>(acc) + q;
-    f32x4 a = ld<true>(av);
+    const f32x4 old = ld<true>(av);
+    f32x4 a = old;
 #pragma unroll
     for (int k = 0; k < K; ++k) a = add4<false>(a, gv[k], 1.0f);
-    if (cnt == 4) {
-        st<true>(av, a);
-    } else {
-        st_f32(acc + 4 * q, a.x);
-        if (cnt > 1) st_f32(acc + 4 * q + 1, a.y);
-        if (cnt > 2) st_f32(acc + 4 * q + 2, a.z);
-    }
+    st<true>(av, cnt == 4 ? a : keep_tail(a, old, cnt));
 }
 
 // Sum of values v[lo .. lo + n) as a balanced binary tree (pairwise summation): the rounding
@@ -1154,11 +1194,14 @@ __global__ __launch_bounds__(kBatchThreads) void k_accum_multi_batched(BatchTabl
             if (a >= tb.arena_elems) continue;
             const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
             const int64_t slot = a - d.shard_off;
-            const int cnt = valid_from(d, r0 + rl, slot, 4);
+            bool gap;
+            const int cnt = vec_cover(d, r0 + rl, slot, gap);
             // gradient element that pairs with arena element a: goff + a
             const int64_t goff = d.full_off + static_cast<int64_t>(r0 + rl) * d.S + slot - a;
-            // a ragged item keeps the wide loads wherever they stay inside the buffers
-            if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems))
+            // ragged and gap vectors are handled whole wherever the wide accesses stay inside the
+            // buffers, so that every accumulator line is written completely (see accum_item_load)
+            if (cnt == 4 || (cnt > 0 && a + 4 <= tb.arena_elems && goff + a + 4 <= tb.full_elems) ||
+                (cnt == 0 && gap && a + 4 <= tb.arena_elems))
                 accum_multi_vec<K, kPieceLoadsNT>(arena, grads, goff, a >> 2, cnt);
             else
                 for (int e = 0; e < cnt; ++e) accum_multi_one<K, ATOMIC>(arena, grads, goff, a + e);
@@ -1461,17 +1504,21 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_drain_batched(BatchTabl
             const int64_t a = (tile << kChunkShift) + a_rel;
             if (a >= tb.arena_elems) continue;
             const TensorDesc d = tile_desc(tb, t_lo, n, a_rel, lds);
-            const int cnt = valid_from(d, r, a - d.shard_off, 4);
+            bool gap;
+            const int cnt = vec_cover(d, r, a - d.shard_off, gap);
             if (cnt == 4) {
                 f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);
                 st<NT>(av, drain_vec<NT>(ld<NT>(av), stage, slot, a, list));
             } else if (cnt > 0 && a + 4 <= tb.arena_elems) {
-                // ragged end of a shard piece: wide loads (every staging slot is at least as
-                // long as the arena rounded up to 8), element stores
-                const f32x4 sum = drain_vec<NT>(ld<NT>(reinterpret_cast<const f32x4 *>(arena + a)), stage, slot, a, list);
-                st_f32(arena + a, sum.x);
-                if (cnt > 1) st_f32(arena + a + 1, sum.y);
-                if (cnt > 2) st_f32(arena + a + 2, sum.z);
+                // ragged end of a shard piece: wide loads (every staging slot is at least as long
+                // as the arena rounded up to 8) and a whole store whose lanes beyond cnt carry
+                // the bits that were read
+                f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);
+                const f32x4 old = ld<NT>(av);
+                st<NT>(av, keep_tail(drain_vec<NT>(old, stage, slot, a, list), old, cnt));
+            } else if (cnt == 0 && gap && a + 4 <= tb.arena_elems) {
+                f32x4 *av = reinterpret_cast<f32x4 *>(arena + a);  // completes the piece's last line
+                st<NT>(av, ld<NT>(av));
             } else {
                 for (int e = 0; e < cnt; ++e) st_f32(arena + a + e, drain_one(ld_f32(arena + a + e), stage, slot, a + e, list));
             }
