@@ -88,19 +88,16 @@ int upload_table(odc_layout_t *L)
     if (L->host.T == 1) return ODC_OK;  // flat kernels need no table
     const odc::HostLayout &H = L->host;
     const size_t T = static_cast<size_t>(H.T);
-    // one blob: descriptors (8-byte aligned data first), then the two tile indices and the
-    // list of element-wise tensors
+    // one blob: descriptors (8-byte aligned data first), then the two tile indices
     const size_t desc_bytes = T * sizeof(odc::TensorDesc);
     const size_t chunk_bytes = H.chunk_first.size() * sizeof(int32_t);
     const size_t full_chunk_bytes = H.full_chunk_first.size() * sizeof(int32_t);
-    const size_t spread_bytes = H.spread.size() * sizeof(int32_t);
-    const size_t total = desc_bytes + chunk_bytes + full_chunk_bytes + spread_bytes;
+    const size_t total = desc_bytes + chunk_bytes + full_chunk_bytes;
     char *staging = new (std::nothrow) char[total];
     if (!staging) return ODC_ERR_NOMEM;
     std::memcpy(staging, H.desc.data(), desc_bytes);
     std::memcpy(staging + desc_bytes, H.chunk_first.data(), chunk_bytes);
     std::memcpy(staging + desc_bytes + chunk_bytes, H.full_chunk_first.data(), full_chunk_bytes);
-    if (spread_bytes) std::memcpy(staging + desc_bytes + chunk_bytes + full_chunk_bytes, H.spread.data(), spread_bytes);
     e = hipMalloc(&L->d_blob, total);
     if (e == hipSuccess) e = hipMemcpy(L->d_blob, staging, total, hipMemcpyHostToDevice);
     delete[] staging;
@@ -113,8 +110,6 @@ int upload_table(odc_layout_t *L)
     L->table.desc = reinterpret_cast<const odc::TensorDesc *>(d);
     L->table.chunk_first = reinterpret_cast<const int32_t *>(d + desc_bytes);
     L->table.full_chunk_first = reinterpret_cast<const int32_t *>(d + desc_bytes + chunk_bytes);
-    L->table.spread = reinterpret_cast<const int32_t *>(d + desc_bytes + chunk_bytes + full_chunk_bytes);
-    L->table.n_spread = static_cast<int32_t>(H.spread.size());
     L->table.gather_tile_tensors = H.gather_tile_tensors;
     L->table.gather_big = H.gather_big;
     L->table.arena_elems = H.arena_elems;

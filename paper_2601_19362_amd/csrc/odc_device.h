@@ -630,8 +630,8 @@ __device__ __forceinline__ int gather_find(const GatherTile<CAP> &lds, int n, in
 // straddling item, a splice.  When one of the two owners belongs to another launch only the
 // elements of the owner served here are stored.  The kernel is deliberately lean: it runs
 // at the rate the number of resident wavefronts allows, so everything rare is kept out of
-// the main path -- tensors with S < 8 (an item spans three or more owners) are skipped here
-// and copied element-wise, one lane per element, by the loop at the end of the kernel.
+// the main path -- tensors with S < 8 (an item spans three or more owners) are skipped there
+// and copied element-wise, one lane per element, by the loop at the end of the tile.
 template <bool NT, int CAP, bool BIG>
 __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb, RankPtrs arenas,
                                                                   uint16_t *__restrict__ full, int r0, int nr,
@@ -641,6 +641,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
     static_assert(kGatherChunks % UG == 0, "tile must hold a whole number of item groups");
     __shared__ GatherTile<CAP> lds;
     if (threadIdx.x < kRanksPerLaunch) lds.base[threadIdx.x] = arenas.p[threadIdx.x];
+    const int wave = static_cast<int>(threadIdx.x) >> 6, lane = static_cast<int>(threadIdx.x) & 63;
     const int64_t nchunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t ntiles = (nchunks + kGatherChunks - 1) / kGatherChunks;
     const int64_t nslots = ((ntiles + (int64_t{8} << block_shift) - 1) >> (block_shift + 3)) << (block_shift + 3);
@@ -709,7 +710,7 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
                 }
                 const uint32_t j = static_cast<uint32_t>(a_rel - lds.rel[k]);
                 const uint32_t numel = lds.numel[k];
-                if (S < 8 || j >= numel) continue;  // element-wise loop below / alignment gap
+                if (S < 8 || j >= numel) continue;  // element-wise loop after the items / alignment gap
                 const uint32_t cnt = numel - j >= 8 ? 8u : numel - j;
                 const uint32_t r = div_owner(j, S);
                 const uint32_t i = j - r * S;
@@ -762,22 +763,24 @@ __global__ __launch_bounds__(kBatchThreads) void k_gather_batched(BatchTable tb,
                 }
             }
         }
-    }
 
-    // Tensors with S < 8: one wavefront per tensor, one lane per element.
-    __syncthreads();  // lds.base is visible even to a workgroup that had no tile
-    const int wave = static_cast<int>(threadIdx.x) >> 6, lane = static_cast<int>(threadIdx.x) & 63;
-    constexpr int kWaves = kBatchThreads / 64;
-    for (int64_t s = static_cast<int64_t>(blockIdx.x) * kWaves + wave; s < tb.n_spread;
-         s += static_cast<int64_t>(gridDim.x) * kWaves) {
-        const TensorDesc d = tb.desc[tb.spread[s]];
-        const uint32_t S = static_cast<uint32_t>(d.S), numel = static_cast<uint32_t>(d.numel);
-        for (uint32_t j = static_cast<uint32_t>(lane); j < numel; j += 64) {
-            const uint32_t r = div_owner(j, S);
-            const uint32_t rl = r - static_cast<uint32_t>(r0);
-            if (rl < static_cast<uint32_t>(nr))
-                st_u16(full + d.full_off + j,
-                       ld_u16(static_cast<const uint16_t *>(lds.base[rl]) + d.shard_off + (j - r * S)));
+        // Tensors with S < 8 that begin in this tile: one wavefront per tensor, one lane per
+        // element.  Done here, next to the items of their neighbours, because their 16-byte
+        // pieces share every cache line with the neighbouring tensors' pieces: in a pass of
+        // their own those lines would be fetched from memory a second time.
+        for (int k = wave; k < n; k += kBatchThreads / 64) {
+            const uint32_t S = lds.S[k];
+            const int32_t rel = lds.rel[k];
+            if (S == 0 || S >= 8 || rel < 0 || rel >= kGatherChunks * kChunkElems) continue;
+            const uint32_t numel = lds.numel[k];
+            uint16_t *dst = full + a0 + rel;
+            const int64_t shard_off = lds.shard_off[k];
+            for (uint32_t j = static_cast<uint32_t>(lane); j < numel; j += 64) {
+                const uint32_t r = div_owner(j, S);
+                const uint32_t rl = r - static_cast<uint32_t>(r0);
+                if (rl < static_cast<uint32_t>(nr))
+                    st_u16(dst + j, ld_u16(static_cast<const uint16_t *>(lds.base[rl]) + shard_off + (j - r * S)));
+            }
         }
     }
 }

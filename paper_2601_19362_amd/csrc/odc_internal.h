@@ -42,12 +42,9 @@ struct BatchTable {
     const int32_t *chunk_first;       // rank-arena space, [arena tiles + 1]: last tensor whose
                                       // shard_off is at or before the tile's first element
     const int32_t *full_chunk_first;  // the same for the full buffer (full_off)
-    const int32_t *spread;            // [n_spread]: tensors with S < 8 (an 8-element item of
-                                      // theirs is spread over more than two owners)
     int64_t arena_elems;
     int64_t full_elems;
     int32_t T;
-    int32_t n_spread;
     int32_t gather_tile_tensors;      // most tensors that intersect one gather tile
     int32_t gather_big;               // 1: some tensor's shard pieces are at least one gather tile long
 };
@@ -61,7 +58,6 @@ struct HostLayout {
     int64_t total_numel = 0;
     std::vector<int32_t> chunk_first;       // built for T > 1
     std::vector<int32_t> full_chunk_first;  // built for T > 1
-    std::vector<int32_t> spread;            // built for T > 1: tensors with S < kAlignElems
     int gather_tile_tensors = 1;            // built for T > 1
     int gather_big = 0;                     // built for T > 1
 };

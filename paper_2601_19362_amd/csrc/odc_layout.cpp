@@ -92,17 +92,10 @@ int build_host_layout(int R, int T, const int64_t *numel, HostLayout *out)
         }
     }
     if (T > 1) {
-        // What the batched gather kernel needs beyond the indices: the tensors it copies
-        // element-wise, and the most tensors any of its tiles holds (sizes its LDS staging).
-        try {
-            for (int t = 0; t < T; ++t) {
-                const int64_t S = L.desc[static_cast<size_t>(t)].S;
-                if (S < kAlignElems) L.spread.push_back(t);
-                if (S >= (int64_t{kGatherChunks} << kChunkShift)) L.gather_big = 1;
-            }
-        } catch (...) {
-            return ODC_ERR_NOMEM;
-        }
+        // What the batched gather kernel needs beyond the indices: whether any shard piece is
+        // a tile long, and the most tensors any of its tiles holds (sizes its LDS staging).
+        for (int t = 0; t < T; ++t)
+            if (L.desc[static_cast<size_t>(t)].S >= (int64_t{kGatherChunks} << kChunkShift)) L.gather_big = 1;
         const int64_t n_chunks = static_cast<int64_t>(L.full_chunk_first.size()) - 1;
         int most = 1;
         for (int64_t c0 = 0; c0 < n_chunks; c0 += kGatherChunks) {

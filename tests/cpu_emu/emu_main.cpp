@@ -189,8 +189,8 @@ int main(int argc, char **argv)
         return 3;
     }
     const size_t arena = static_cast<size_t>(H.arena_elems), full_n = static_cast<size_t>(H.full_elems);
-    BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.spread.data(), H.arena_elems,
-                  H.full_elems, H.T, static_cast<int32_t>(H.spread.size()), H.gather_tile_tensors, H.gather_big};
+    BatchTable tb{H.desc.data(), H.chunk_first.data(), H.full_chunk_first.data(), H.arena_elems,
+                  H.full_elems, H.T, H.gather_tile_tensors, H.gather_big};
     const bool flat = H.T == 1;
     const int64_t S = H.desc[0].S, N = H.desc[0].numel;
 
