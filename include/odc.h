@@ -189,7 +189,8 @@ int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const vo
  *
  *   staging_shards [R] host array of device pointers: owner r's buffer, bf16, R slots of
  *                  odc_stage_slot_elems() elements (client w's slot starts at w * slot and
- *                  mirrors the rank arena); 16-byte aligned
+ *                  mirrors the rank arena; what a slot holds outside the valid elements of its
+ *                  pieces is unspecified and never used); 16-byte aligned
  *   flags          device int32[odc_stage_flag_count()] = R*R slot states (owner-major: owner r,
  *                  client w at r*R + w; 0 empty, 1 full, 2 being written) + 1 counter of refused pushes
  *   snapshot       device int32[odc_stage_snapshot_count()], scratch owned by the caller; a

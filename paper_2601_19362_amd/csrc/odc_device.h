@@ -1364,14 +1364,10 @@ __global__ __launch_bounds__(kBatchThreads) void k_stage_push_batched(BatchTable
 #pragma unroll
         for (int u = 0; u < kPushChunks; ++u) {
             const int64_t a = a0 + 8 * (u * kBatchThreads + static_cast<int>(threadIdx.x));
-            if (cnt[u] == 8) {
-                st<NT>(reinterpret_cast<u32x4 *>(dst + a), v[u]);
-            } else if (cnt[u] > 0) {
-                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                for (int e = 0; e < 7; ++e)
-                    if (e < cnt[u]) st_u16(dst + a + e, static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1))));
-            }
+            // A ragged item is stored whole as well: its spare lanes fall into the alignment gap
+            // behind the piece, which in a staging slot belongs to nobody (the drain never takes
+            // them), and a slot written in whole 16-byte vectors has no partly written sector.
+            if (cnt[u] > 0) st<NT>(reinterpret_cast<u32x4 *>(dst + a), v[u]);
         }
     }
 }
