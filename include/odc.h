@@ -319,6 +319,11 @@ int odc_retrieve_grads_wide(const odc_layout_t *layout, const void *const *accum
  *                                them) but no other group's (ODC_ERR_INVALID_ARG).  Follow with
  *                                odc_retrieve_grads on out_shards.  Enqueues one kernel per 16
  *                                owners and per 8 groups.  (groups + 1) * 4 bytes per valid element.
+ *                                The same call serves contributions that arrive concurrently on
+ *                                one device without atomics: give every stream an accumulator
+ *                                set of its own (ordered calls, one set per stream) and sum the
+ *                                sets here; the result does not depend on how the streams
+ *                                interleave.
  */
 #define ODC_MAX_GROUPS 1024
 int odc_hybrid_group_of(const odc_layout_t *layout, int groups, int world_worker);

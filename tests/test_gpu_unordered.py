@@ -161,6 +161,58 @@ def test_unordered_at_stress_contribution_count(oracle):
     L.close()
 
 
+def test_concurrent_streams_with_private_accumulators(oracle):
+    """The other way to take contributions that arrive concurrently: every stream adds into an
+    accumulator set of its own with the ordered kernel (no atomics, full rate) and the sets are
+    summed at the minibatch end by the group reduction of Section 6.1.  Whatever the streams'
+    interleaving, the result is one fixed sequence of binary32 additions, so it is compared
+    with the oracle bit for bit, and with the float64 reference under the bound that follows
+    from the counts: (most contributions in one set - 1) + (sets - 1) roundings."""
+    wl = inputs.workload("1.5b")
+    N, R, K = wl.numel[0], wl.R, 4
+    seq = contributions(inputs.microbatch_counts(wl))
+    print(f"private accumulators 1.5b: N={N} R={R} C={len(seq)} sets={K}", flush=True)
+    L = odc.Layout(R, [N])
+    S = L.shard_elems(0)
+    dev = torch.device("cuda")
+    accs = [torch.full((S,), 3.25, dtype=torch.float32, device=dev) for _ in range(K * R)]
+    accs_h = [[np.full(S, 3.25, dtype=np.float32) for _ in range(R)] for _ in range(K)]
+    streams = [torch.cuda.Stream() for _ in range(K)]
+    for k in range(K):
+        L.reset_accum(accs[k * R:(k + 1) * R])
+        oracle.reset(accs_h[k], N, nthreads=THREADS)
+    torch.cuda.synchronize()
+    pinned = torch.empty(N, dtype=torch.int16, pin_memory=True)
+    g_h = pinned.numpy().view(np.uint16)
+    tot, mag = np.zeros(N), np.zeros(N)
+    pool, per_set = [], [0] * K
+    for i, (w, m) in enumerate(seq):
+        k = i % K
+        g = inputs.device_normal_bf16(N, wl.grad_sigma, 9700 + 64 * w + m, dev)
+        torch.cuda.current_stream().synchronize()            # g is complete before another stream reads it
+        L.scatter_accumulate(g, accs[k * R:(k + 1) * R], w, m, stream=streams[k])
+        per_set[k] += 1
+        pinned.copy_(g.view(torch.int16))
+        oracle.accumulate(g_h, accs_h[k], N, nthreads=THREADS)
+        oracle.fp64_add(g_h, tot, mag, nthreads=THREADS)
+        pool.append(g)                                       # keep alive until the streams are done
+        if len(pool) > 6:
+            torch.cuda.synchronize()
+            pool.clear()
+    torch.cuda.synchronize()
+    out = [torch.full((S,), -1.0, dtype=torch.float32, device=dev) for _ in range(R)]
+    out_h = [np.full(S, -1.0, dtype=np.float32) for _ in range(R)]
+    L.reduce_groups(K, accs, out)
+    oracle.reduce_groups(accs_h, out_h, N, nthreads=THREADS)
+    torch.cuda.synchronize()
+    for r in range(R):
+        assert np.array_equal(out[r].cpu().numpy().view(np.uint32), out_h[r].view(np.uint32)), f"reduced shard of owner {r}"
+    worst = check_against_fp64(out, tot, mag, N, S, f"private accumulators 1.5b C={len(seq)} sets={K}")
+    roundings = max(per_set) - 1 + K - 1
+    assert roundings * 2.0 ** -24 < TOL and worst <= roundings * 2.0 ** -24 * (1 + 1e-6)
+    L.close()
+
+
 # ----------------------------------------------------------------------------- wide accumulators
 def wide_case(oracle, numel, R, C, seed, streams=3):
     """reset, C contributions in scrambled order on several streams, both retrievals; the binary64
