@@ -4,8 +4,11 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstring>
+#include <functional>
 #include <new>
+#include <vector>
 
 #include "odc_internal.h"
 
@@ -558,10 +561,17 @@ int odc_reduce_groups(const odc_layout_t *L, int groups, const void *const *grou
     }
     // the sum may replace group 0's shards; a later group's shard would be overwritten by the
     // first pass before a later pass reads it
-    for (int k = 1; k < groups; ++k)
-        for (int r = 0; r < R; ++r)
-            for (int q = 0; q < R; ++q)
-                if (group_accum_shards[static_cast<size_t>(k) * R + r] == out_shards[q]) return ODC_ERR_INVALID_ARG;
+    if (groups > 1) {
+        try {
+            std::vector<const void *> outs(out_shards, out_shards + R);
+            std::sort(outs.begin(), outs.end(), std::less<const void *>());
+            for (size_t i = static_cast<size_t>(R); i < static_cast<size_t>(groups) * R; ++i)
+                if (std::binary_search(outs.begin(), outs.end(), group_accum_shards[i], std::less<const void *>()))
+                    return ODC_ERR_INVALID_ARG;
+        } catch (...) {
+            return ODC_ERR_NOMEM;
+        }
+    }
     rc = check_device(L);
     if (rc != ODC_OK) return rc;
     const odc::BatchTable *tb = H.T == 1 ? nullptr : &L->table;

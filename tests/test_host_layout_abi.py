@@ -149,6 +149,61 @@ def test_launch_argument_errors_are_found_before_any_launch():
     L.close()
 
 
+def test_hybrid_wide_and_staging_argument_errors_are_found_on_the_host():
+    """The later entry points validate before they launch too (host-only layout, fake addresses)."""
+    import ctypes
+    L = odc.Layout(4, [1000], host_only=True)
+    lib = odc.lib()
+    good = [0x1000, 0x2000, 0x3000, 0x4000]
+    two = good + [0x5000, 0x6000, 0x7000, 0x9000]                      # two groups of four owners
+    out = [0xA000, 0xB000, 0xC000, 0xD000]
+    assert odc.reduce_groups_rc(L, 2, two, out, stream=0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.reduce_groups_rc(L, 2, two, good, stream=0) == odc.ODC_ERR_NO_DEVICE          # into group 0: allowed
+    assert odc.reduce_groups_rc(L, 2, two, [0xA000, 0x7000, 0xC000, 0xD000], stream=0) == odc.ODC_ERR_INVALID_ARG  # a later group's shard
+    assert odc.reduce_groups_rc(L, 2, two, two[4:], stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.reduce_groups_rc(L, 0, [], out, stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_reduce_groups(L.handle, odc.ODC_MAX_GROUPS + 1, (ctypes.c_void_p * 8)(*two), (ctypes.c_void_p * 4)(*out), None) == odc.ODC_ERR_INVALID_ARG
+    assert odc.reduce_groups_rc(L, 2, two[:5] + [0x6004] + two[6:], out, stream=0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.reduce_groups_rc(L, 2, two, None, stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert L.hybrid_group_of(2, 0) == 0 and L.hybrid_group_of(2, 7) == 1 and L.hybrid_group_of(2, 8) == -1
+    assert L.hybrid_group_of(2, -1) == -1 and L.hybrid_group_of(0, 0) == -1
+    sah = odc.scatter_accumulate_hybrid_rc
+    assert sah(L, 2, 0x8000, two, 5, 0, stream=0) == odc.ODC_ERR_NO_DEVICE
+    assert sah(L, 2, 0x8000, two, 8, 0, stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert sah(L, 2, 0x8002, two, 5, 0, stream=0) == odc.ODC_ERR_ALIGNMENT
+    arr, full = (ctypes.c_void_p * 8)(*two), ctypes.c_void_p(0x8000)
+    assert lib.odc_gather_hybrid(L.handle, 2, arr, 7, full, None) == odc.ODC_ERR_NO_DEVICE
+    assert lib.odc_gather_hybrid(L.handle, 2, arr, 8, full, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_gather_hybrid(L.handle, 2, None, 0, full, None) == odc.ODC_ERR_INVALID_ARG
+
+    a4 = (ctypes.c_void_p * 4)(*good)
+    o4 = (ctypes.c_void_p * 4)(*out)
+    bad4 = (ctypes.c_void_p * 4)(0x1000, 0x2008, 0x3000, 0x4000)
+    assert lib.odc_reset_accum_wide(L.handle, a4, None) == odc.ODC_ERR_NO_DEVICE
+    assert lib.odc_reset_accum_wide(L.handle, None, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_reset_accum_wide(L.handle, bad4, None) == odc.ODC_ERR_ALIGNMENT
+    assert lib.odc_scatter_accumulate_wide(L.handle, 0x8000, a4, None) == odc.ODC_ERR_NO_DEVICE
+    assert lib.odc_scatter_accumulate_wide(L.handle, None, a4, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_scatter_accumulate_wide(L.handle, 0x8008, a4, None) == odc.ODC_ERR_ALIGNMENT
+    assert lib.odc_retrieve_grads_wide(L.handle, a4, o4, 1.0, odc.ODC_OUT_BF16, None) == odc.ODC_ERR_NO_DEVICE
+    assert lib.odc_retrieve_grads_wide(L.handle, a4, o4, 1.0, 7, None) == odc.ODC_ERR_INVALID_ARG
+    assert lib.odc_retrieve_grads_wide(L.handle, a4, None, 1.0, odc.ODC_OUT_F32, None) == odc.ODC_ERR_INVALID_ARG
+
+    flags = 0xE000
+    assert odc.stage_push_rc(L, 0x8000, good, flags, 0, stream=0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.stage_push_rc(L, 0x8000, good, flags, 4, stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.stage_push_rc(L, 0x8000, good, 0xE004, 0, stream=0) == odc.ODC_ERR_ALIGNMENT
+    assert odc.stage_drain_rc(L, good, flags, 0xF000, out, stream=0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.stage_drain_rc(L, good, flags, None, out, stream=0) == odc.ODC_ERR_INVALID_ARG
+    assert odc.stage_drain_noalloc_rc(L, good, flags, out, stream=0) == odc.ODC_ERR_NO_DEVICE
+    assert odc.stage_drain_noalloc_rc(L, good, None, out, stream=0) == odc.ODC_ERR_INVALID_ARG
+    L.close()
+    big = odc.Layout(odc.ODC_NOALLOC_MAX_RANKS + 1, [100_000], host_only=True)
+    ptrs = [0x1000 + 0x100 * r for r in range(big.R)]
+    assert odc.stage_drain_noalloc_rc(big, ptrs, flags, ptrs, stream=0) == odc.ODC_ERR_TOO_LARGE
+    big.close()
+
+
 def test_probe_and_tune_argument_errors():
     lib = odc.lib()
     assert lib.odc_probe_copy(None, 0x1000, 16, None) == odc.ODC_ERR_INVALID_ARG
