@@ -1,5 +1,6 @@
-// Kernel launchers for the ODC hot path (gfx950).  The kernels themselves are in
-// odc_device.h; this file only picks an instantiation and a grid.
+// Kernel launchers for the ODC hot path (gfx950).  The kernels themselves are in the
+// odc_dev_*.h headers (one per family, all included by odc_device.h); this file only picks an
+// instantiation and a grid.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

@@ -1,8 +1,9 @@
 """The kernel source run on the CPU, one thread at a time, under AddressSanitizer and UBSan.
 
-tests/cpu_emu/emu_main.cpp compiles paper_2601_19362_amd/csrc/odc_device.h (the real kernels)
-against a small host shim.  Every rank buffer is an exactly-sized heap block, so an index
-error in a kernel shows up here, on the CPU, as a sanitizer report instead of a GPU fault.
+tests/cpu_emu/emu_main.cpp compiles paper_2601_19362_amd/csrc/odc_device.h (the real kernels,
+one odc_dev_*.h header per family) against a small host shim.  Every rank buffer is an
+exactly-sized heap block, so an index error in a kernel shows up here, on the CPU, as a
+sanitizer report instead of a GPU fault.
 The outputs are compared with the CPU oracle bit for bit.  This checks the kernels' indexing
 and arithmetic logic, not the GPU build: parity of the HIP path proper is tests/test_gpu_*.py.
 """
