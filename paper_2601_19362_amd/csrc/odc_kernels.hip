@@ -279,11 +279,17 @@ int launch_stage_push_batched(const BatchTable &tb, void *const *staging, int r0
     const RankPtrs rp = pack(staging, nr);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t chunks = (tb.arena_elems + kChunkElems - 1) >> kChunkShift;
-    const dim3 grid(batched_grid_x(t, (chunks + kPushChunks - 1) / kPushChunks), static_cast<unsigned>(nr));
-    ODC_DISPATCH_NT(t.nontemporal != 0,
-                    (k_stage_push_batched<NT_><<<grid, kBatchThreads, 0, s>>>(
-                        tb, rp, static_cast<const uint16_t *>(grad), static_cast<const int32_t *>(flags), slot, R, r0,
-                        worker)));
+    const int64_t tiles = (chunks + kPushChunks - 1) / kPushChunks;
+    const int rg = rank_group(t, tb, tiles, nr, 2) >= 2 ? 2 : 1;
+    const dim3 grid(batched_grid_x(t, tiles), static_cast<unsigned>((nr + rg - 1) / rg));
+    const uint16_t *g = static_cast<const uint16_t *>(grad);
+    const int32_t *f = static_cast<const int32_t *>(flags);
+    if (rg == 2)
+        ODC_DISPATCH_NT(t.nontemporal != 0, (k_stage_push_batched<NT_, 2><<<grid, kBatchThreads, 0, s>>>(
+                                                tb, rp, g, f, slot, R, r0, nr, worker)));
+    else
+        ODC_DISPATCH_NT(t.nontemporal != 0, (k_stage_push_batched<NT_, 1><<<grid, kBatchThreads, 0, s>>>(
+                                                tb, rp, g, f, slot, R, r0, nr, worker)));
     return finish();
 }
 
@@ -303,14 +309,14 @@ int launch_stage_raise(void *flags, int R, int worker, void *stream)
 
 int launch_stage_snapshot(const void *flags, void *snapshot, int R, void *stream)
 {
-    k_stage_snapshot<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(
+    k_stage_snapshot<<<dim3(static_cast<unsigned>(R)), 64, 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<const int32_t *>(flags), static_cast<int32_t *>(snapshot), R);
     return finish();
 }
 
 int launch_stage_clear(void *flags, const void *snapshot, int R, void *stream)
 {
-    k_stage_clear<<<dim3((R + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(
+    k_stage_clear<<<dim3(static_cast<unsigned>(R)), 64, 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<int32_t *>(flags), static_cast<const int32_t *>(snapshot), R);
     return finish();
 }

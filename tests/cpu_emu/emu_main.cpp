@@ -404,15 +404,21 @@ int main(int argc, char **argv)
                 } else {
                     const int64_t chunks = ((tb.arena_elems + kChunkElems - 1) >> kChunkShift);
                     const int64_t tiles = (chunks + kPushChunks - 1) / kPushChunks;
-                    const unsigned groups = static_cast<unsigned>(nr);
-                    EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
-                               k_stage_push_batched<NT_>(tb, rs, g, flags, slot, R, r0, worker);
-                           }));
+                    const int prg = rg >= 2 ? 2 : 1;  // owners per workgroup of the push kernel
+                    const unsigned groups = static_cast<unsigned>((nr + prg - 1) / prg);
+                    if (prg == 2)
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
+                                   k_stage_push_batched<NT_, 2>(tb, rs, g, flags, slot, R, r0, nr, worker);
+                               }));
+                    else
+                        EMU_NT(nt, run_grid_threaded(kBatchThreads, grid_x_for(tiles, 1, cap), groups, [&] {
+                                   k_stage_push_batched<NT_, 1>(tb, rs, g, flags, slot, R, r0, nr, worker);
+                               }));
                 }
             }
         };
         auto push_raise = [&](int worker) { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_raise(flags, R, worker); }); };
-        auto drain_snapshot = [&] { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_snapshot(flags, snap, R); }); };
+        auto drain_snapshot = [&] { run_grid_threaded(64, static_cast<unsigned>(R), 1, [&] { k_stage_snapshot(flags, snap, R); }); };
         auto drain_add = [&] {
             for (int r0 = 0; r0 < R; r0 += kRanksPerLaunch) {
                 const int nr = R - r0 < kRanksPerLaunch ? R - r0 : kRanksPerLaunch;
@@ -434,7 +440,7 @@ int main(int argc, char **argv)
                 }
             }
         };
-        auto drain_clear = [&] { run_grid(64, (R + 63) / 64, 1, [&] { k_stage_clear(flags, snap, R); }); };
+        auto drain_clear = [&] { run_grid(64, static_cast<unsigned>(R), 1, [&] { k_stage_clear(flags, snap, R); }); };
         // Steps: "pW" whole push by client W; its three kernels one by one: "cW" claim (takes the
         // next grad<k>.u16), "xW" copy or "xW:k:n" only the copy workgroups congruent to k mod n,
         // "rW" raise; "d" whole drain, or its kernels "s" snapshot, "a" add, "z" clear.

@@ -254,8 +254,8 @@ def test_emulated_fused_unordered_sums_every_gradient_once(oracle, emu, tmp_path
 @pytest.mark.parametrize("numel,R", [([7], 3), ([8 * 1024 * 3 + 5], 4), ([4099], 8), ([1], 64),
                                      ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8), ([30000, 17, 2048, 2049], 5),
                                      ([5] * 66, 66), ([40_000, 9, 20_001, 3], 2)])
-@pytest.mark.parametrize("nt,cap", [(1, 0), (0, 2)])
-def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
+@pytest.mark.parametrize("nt,cap,rg", [(1, 0, 1), (0, 2, 2)])
+def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap, rg):
     """Pushes into per-client slots, drains in ascending client order, refusal of a push into
     a slot that is still full; compared with the oracle's bookkeeping model."""
     S, so, fo, arena, full_n = placement(numel, R)
@@ -277,7 +277,7 @@ def test_emulated_staging(oracle, emu, tmp_path, numel, R, nt, cap):
         else:
             model.drain(acc)
     script = ",".join(f"p{w}" if kind == "p" else "d" for kind, w in steps)
-    run(emu, tmp_path, "stage", R, nt=nt, cap=cap, script=script)
+    run(emu, tmp_path, "stage", R, nt=nt, cap=cap, rg=rg, script=script)   # rg: owners per workgroup of the push
     got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
     flags = np.fromfile(tmp_path / "flags.out", dtype=np.int32)
@@ -388,7 +388,7 @@ def test_emulated_staging_interleavings(oracle, emu, tmp_path, numel, R, script)
                 model.end_drain()
         elif kind == "z":
             model.end_drain()
-    run(emu, tmp_path, "stage", R, script=script)
+    run(emu, tmp_path, "stage", R, rg=1 + len(script) % 2, script=script)
     got = np.fromfile(tmp_path / "acc.out", dtype=np.float32)
     assert np.array_equal(got.view(np.uint32), np.concatenate(acc).view(np.uint32))
     flags = np.fromfile(tmp_path / "flags.out", dtype=np.int32)
