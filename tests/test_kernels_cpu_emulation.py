@@ -416,7 +416,7 @@ def random_layout(seed):
     return sizes, R
 
 
-@pytest.mark.parametrize("seed", range(20))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("ODC_EMU_RANDOM_LAYOUTS", "20"))))   # more on request
 def test_emulated_random_layouts(oracle, emu, emu_low_limit, tmp_path, seed):
     """Gather (both builds), reset, one ordered and one unordered contribution and a retrieval on
     a random layout; every buffer compared in full with the oracle."""
