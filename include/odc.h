@@ -20,7 +20,9 @@
  *     pointers; the library copies them during the call and keeps no reference.
  *   - Every device base pointer (each shard, the full buffer, each accumulator shard, the
  *     gradient) must be 16-byte aligned, else ODC_ERR_ALIGNMENT.  Interior boundaries
- *     (r * S_t) may fall anywhere; that is the library's business.
+ *     (r * S_t) may fall anywhere; that is the library's business.  The kernels are
+ *     fastest when the bases are 128-byte aligned (a wavefront then writes whole cache
+ *     lines), which device allocators give anyway.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Launch
  *     calls only enqueue work on it and return: they never synchronise the device and never
  *     allocate or free device memory.  On the host, the ordered mode takes the layout's mutex
@@ -188,9 +190,10 @@ int odc_scatter_accumulate_multi(const odc_layout_t *layout, int count, const vo
  * (no kernel ever waits).
  *
  *   staging_shards [R] host array of device pointers: owner r's buffer, bf16, R slots of
- *                  odc_stage_slot_elems() elements (client w's slot starts at w * slot and
- *                  mirrors the rank arena; what a slot holds outside the valid elements of its
- *                  pieces is unspecified and never used); 16-byte aligned
+ *                  odc_stage_slot_elems() elements (the rank arena rounded up to a multiple of
+ *                  64 elements; client w's slot starts at w * slot and mirrors the rank arena;
+ *                  what a slot holds outside the valid elements of its pieces is unspecified
+ *                  and never used); 16-byte aligned, fastest when 128-byte aligned
  *   flags          device int32[odc_stage_flag_count()] = R*R slot states (owner-major: owner r,
  *                  client w at r*R + w; 0 empty, 1 full, 2 being written) + 1 counter of refused pushes
  *   snapshot       device int32[odc_stage_snapshot_count()], scratch owned by the caller; a

@@ -333,9 +333,13 @@ int odc_scatter_accumulate_multi(const odc_layout_t *L, int count, const void *c
     return rc;
 }
 
+// A client's slot: the rank arena rounded up to whole 128-byte cache lines of bf16, so that
+// every slot of a line-aligned staging buffer starts on a line (the copy kernels' wavefronts
+// then write whole lines).
 static int64_t stage_slot(const odc_layout_t *L)
 {
-    return (L->host.arena_elems + odc::kAlignElems - 1) / odc::kAlignElems * odc::kAlignElems;
+    return (L->host.arena_elems + odc::kStageSlotAlignElems - 1) / odc::kStageSlotAlignElems *
+           odc::kStageSlotAlignElems;
 }
 
 int64_t odc_stage_slot_elems(const odc_layout_t *L) { return L ? stage_slot(L) : -1; }

@@ -59,8 +59,12 @@ __global__ __launch_bounds__(TPB) void k_gather_flat(RankPtrs shards, uint16_t *
     if (valid <= 0) return;
     const uint16_t *__restrict__ src = static_cast<const uint16_t *>(shards.p[blockIdx.y]);
     uint16_t *__restrict__ dst = full + base;
-    // Elements before the first 16-byte boundary of the destination.
-    int64_t head = static_cast<int64_t>((16u - (reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) >> 1;
+    // Elements before the first 128-byte boundary of the destination: every wavefront's store
+    // then covers whole cache lines.  (Aligning the items to 16 bytes only is enough for
+    // correctness, but when an owner's range starts off a line boundary each wavefront's
+    // kilobyte begins and ends in a line it shares with its neighbours, and those partly
+    // written lines cost a fifth of the rate: 5.5 against 6.7 TB/s on a 233 M-element tensor.)
+    int64_t head = static_cast<int64_t>((128u - (reinterpret_cast<uintptr_t>(dst) & 127u)) & 127u) >> 1;
     if (head > valid) head = valid;
     const int64_t nvec = (valid - head) >> 3;
     const int tail = static_cast<int>((valid - head) & 7);

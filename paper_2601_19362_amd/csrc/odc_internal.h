@@ -15,6 +15,8 @@ constexpr int kRanksPerLaunch = 64;
 // Every tensor starts at a multiple of this many elements inside a rank arena and inside
 // the full buffer: 16 bytes of bf16, 32 bytes of binary32.
 constexpr int64_t kAlignElems = 8;
+// A staging slot is a whole number of 128-byte lines of bf16.
+constexpr int64_t kStageSlotAlignElems = 64;
 // Rank-arena elements per entry of the coarse tensor-lookup index (power of two).
 constexpr int kChunkShift = 11;
 

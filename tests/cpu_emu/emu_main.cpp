@@ -366,7 +366,7 @@ int main(int argc, char **argv)
         // script: comma-separated steps (see below); the k-th push started reads grad<k>.u16
         std::vector<float> all = read_file<float>(dir + "/acc.f32");
         if (all.size() != arena * static_cast<size_t>(R)) return 4;
-        const int64_t slot = (H.arena_elems + kAlignElems - 1) / kAlignElems * kAlignElems;
+        const int64_t slot = (H.arena_elems + kStageSlotAlignElems - 1) / kStageSlotAlignElems * kStageSlotAlignElems;
         std::vector<float *> accs(static_cast<size_t>(R));
         std::vector<uint16_t *> stages(static_cast<size_t>(R));
         for (int r = 0; r < R; ++r) {

@@ -64,7 +64,8 @@ def test_tiny_config(oracle):
 
 @pytest.mark.parametrize("N,R", [(1, 1), (1, 64), (7, 3), (64, 64), (65, 64), (1000, 7), (4099, 8),
                                  (8 * 1024 * 3 + 5, 4), (524_309, 2), (1_000_003, 33),
-                                 (4 * 1024 * 1024, 8), (3_000_001, 16), (350, 70)])
+                                 (4 * 1024 * 1024, 8), (3_000_001, 16), (350, 70),
+                                 (8 * 1_000_001 - 3, 8)])   # S = 1,000,001: owner r's source shifted by 16 - 2r bytes
 def test_single_tensor_shapes(oracle, N, R):
     M = [1 + (w % 3 == 0) for w in range(R)]
     run_case(oracle, [N], R, contributions(M)[:6], seed=N % 1000 + R)

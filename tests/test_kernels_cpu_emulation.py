@@ -91,6 +91,7 @@ CASES = [
     ([1], 1), ([1], 64), ([7], 3), ([64], 64), ([65], 64), ([1000], 7), ([4099], 8),
     ([8 * 1024 * 3 + 5], 4),          # several full tiles + ragged tail, misaligned boundaries
     ([262_148 * 2 + 13], 2),
+    ([8 * 4097 - 3], 8),              # S = 4097: owner r's source is shifted by 16 - 2r bytes, every shift once
     ([1, 5, 8, 9, 64, 100, 1, 777, 3, 4096, 63], 8),
     ([3, 1, 1, 2, 70, 5000, 2, 2, 129, 1], 64),
     ([30000, 17, 2048, 2049], 5),
