@@ -27,7 +27,8 @@
  *     calls only enqueue work on it and return: they never synchronise the device and never
  *     allocate or free device memory.  On the host, the ordered mode takes the layout's mutex
  *     for the duration of the call and, the first time it sees an accumulator set, allocates
- *     one small bookkeeping node (see ODC_ORDERED below); nothing else allocates.
+ *     one small bookkeeping node (see ODC_ORDERED below); odc_reduce_groups sorts a temporary
+ *     host copy of its R output pointers; nothing else allocates.
  *     A call enqueues one kernel per group of up to 64 ranks, so exactly one kernel for
  *     R <= 64, for any number of tensors T.  With R > 64, if a later group's launch fails
  *     (ODC_ERR_HIP) the earlier groups' kernels are already enqueued: the accumulators are then
