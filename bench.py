@@ -44,6 +44,10 @@ def parse_args():
                     help="config: the workload's own per-rank microbatch counts; lb-mini / lb-micro: draw a "
                          "global minibatch of 16 samples per rank from the long-tailed length law and plan it "
                          "with the library's Karmarkar-Karp packing (paper Section 4)")
+    ap.add_argument("--measure-traffic", action="store_true",
+                    help="before anything else, run this same command twice under rocprofv3 --pmc (FETCH_SIZE, "
+                         "then WRITE_SIZE; one step each) and report the HBM bytes per accumulate launch they "
+                         "show as roofline.traffic (adds a minute or two)")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="measured HBM bytes per accumulate launch (from rocprofv3 --pmc runs); "
                          "default: the figure recorded in profiles/ for the 7b workload")
@@ -70,6 +74,92 @@ def recorded_traffic(workload, tune):
     except OSError:
         pass
     return None, "not measured (profile summary not found)"
+
+
+def measure_traffic(args):
+    """HBM bytes per ordered-accumulate launch from two child runs of this file under
+    `rocprofv3 --pmc` (FETCH_SIZE, then WRITE_SIZE: one counter set per run, no trace domain),
+    each scaled by what the same counter shows for the plain copy kernel, whose size the child
+    prints.  Must be called before this process loads the HIP library.  Returns (bytes, source)."""
+    import csv
+    import glob
+    import shutil
+    import signal
+    import subprocess
+    import tempfile
+
+    exe = shutil.which("rocprofv3")
+    if exe is None:
+        return None, "not measured (rocprofv3 not found)"
+    # A profiler around this very process has initialised the GPU already: starting the child
+    # runs from here would not be safe, and counters cannot nest anyway.
+    under_profiler = any(k.startswith("ROCPROF_") for k in os.environ) or any(
+        "rocprof" in os.environ.get(var, "").lower() for var in ("LD_PRELOAD", "HSA_TOOLS_LIB", "ROCP_TOOL_LIBRARIES"))
+    if under_profiler:
+        return None, "not measured (this process itself runs under a profiler)"
+    here = os.path.abspath(__file__)
+    tmp = tempfile.mkdtemp(prefix="odc_pmc_", dir="/tmp")
+    child = [sys.executable, here, "--workload", args.workload, "--steps", "1", "--warmup", "0",
+             "--no-cpu-baseline", "--microbatch-plan", args.microbatch_plan]
+    if args.layers > 0:
+        child += ["--layers", str(args.layers)]
+    for kv in args.tune:
+        child += ["--tune", kv]
+    per_kernel = {}
+    copy_bytes = None
+    try:
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            out = os.path.join(tmp, counter)
+            cmd = [exe, "--pmc", counter, "--output-format", "csv", "-d", out, "-o", "b", "--"] + child
+            proc = subprocess.Popen(cmd, cwd="/tmp", env={**os.environ, "TMPDIR": "/tmp"}, stdout=subprocess.PIPE,
+                                    stderr=subprocess.DEVNULL, start_new_session=True, text=True)
+            try:
+                child_out, _ = proc.communicate(timeout=300)
+                rc = proc.returncode
+            except subprocess.TimeoutExpired:
+                os.killpg(proc.pid, signal.SIGKILL)   # the session this call started, nothing else
+                proc.wait()
+                return None, f"not measured (the {counter} run did not end within 300 s)"
+            for line in child_out.splitlines():
+                if line.startswith('{"metric"'):
+                    copy_bytes = json.loads(line)["kernels"].get("plain_copy_bytes_each_way")
+            files = glob.glob(os.path.join(out, "**", "*counter_collection.csv"), recursive=True)
+            if rc != 0 or not files:
+                return None, f"not measured (the {counter} run failed, exit code {rc})"
+            sums = {}
+            with open(files[0]) as f:
+                for row in csv.DictReader(f):
+                    if row["Counter_Name"] != counter:
+                        continue
+                    name = row["Kernel_Name"]
+                    tot, n = sums.get(name, (0.0, 0))
+                    sums[name] = (tot + float(row["Counter_Value"]), n + 1)
+            per_kernel[counter] = sums
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+
+    def pick(counter, what):
+        """(mean KiB per dispatch, dispatches) of the kernel of kind `what` with the most dispatches."""
+        best = None
+        for name, (tot, n) in per_kernel[counter].items():
+            if what == "copy":
+                hit = "k_probe_copy" in name
+            else:   # the ordered, unweighted accumulate is by far the most frequent accumulate kernel
+                hit = "k_accum_flat<" in name or "k_accum_batched<" in name
+            if hit and (best is None or n > best[1]):
+                best = (tot / n, n)
+        return best
+
+    fetch_acc, write_acc = pick("FETCH_SIZE", "accum"), pick("WRITE_SIZE", "accum")
+    fetch_cp, write_cp = pick("FETCH_SIZE", "copy"), pick("WRITE_SIZE", "copy")
+    if not (fetch_acc and write_acc and fetch_cp and write_cp and copy_bytes) or fetch_cp[0] <= 0 or write_cp[0] <= 0:
+        return None, "not measured (kernels not found in the counter output)"
+    copy_kib = copy_bytes / 1024.0
+    f_fac, w_fac = fetch_cp[0] / copy_kib, write_cp[0] / copy_kib
+    traffic = (fetch_acc[0] / f_fac + write_acc[0] / w_fac) * 1024.0
+    return traffic, (f"measured by this invocation: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on two child runs of "
+                     f"this command (1 step each, {fetch_acc[1]} / {write_acc[1]} accumulate dispatches), scaled by "
+                     f"the plain copy kernel of {copy_bytes} B each way (factors {f_fac:.5f} / {w_fac:.5f})")
 
 
 def build_state(w, layers, torch, odc, inputs):
@@ -235,6 +325,11 @@ def main():
         print("bench.py: this build runs on ONE GPU (one GPU holds every logical rank's shard; "
               "no collectives, no peer access); --gpus must be 1", file=sys.stderr)
         return 2
+    measured = None
+    if args.measure_traffic:
+        # first of all: the child runs own the GPU one after the other; this process has neither
+        # loaded a HIP library nor touched the GPU yet
+        measured = measure_traffic(args)
     import torch
 
     from paper_2601_19362_amd import binding as odc
@@ -339,6 +434,11 @@ def main():
 
     if args.traffic_bytes is not None:
         traffic, traffic_source = args.traffic_bytes, "given on the command line (--traffic-bytes)"
+    elif measured is not None and measured[0] is not None:
+        traffic, traffic_source = round(measured[0]), measured[1]
+    elif measured is not None:
+        traffic, traffic_source = recorded_traffic(args.workload, args.tune)
+        traffic_source = f"{measured[1]}; {traffic_source}"
     else:
         traffic, traffic_source = recorded_traffic(args.workload, args.tune)
     out = {
@@ -375,6 +475,7 @@ def main():
             "retrieve_f32_GBs": {"median": round(8 * total / r32_med / 1e6, 1), "best": round(8 * total / r32_min / 1e6, 1)},
             "retrieve_bf16_GBs": {"median": round(6 * total / r16_med / 1e6, 1), "best": round(6 * total / r16_min / 1e6, 1)},
             "plain_copy_GBs": {"median": round(2 * nbytes_copy / cp_med / 1e6, 1), "best": round(2 * nbytes_copy / cp_min / 1e6, 1)},
+            "plain_copy_bytes_each_way": nbytes_copy,
         },
     }
     if not args.no_cpu_baseline:
