@@ -529,6 +529,89 @@ def test_staging_repeated_pushes_race_drains_on_another_stream():
     case.close()
 
 
+def test_host_daemon_polls_the_flags_and_accumulates_on_receipt():
+    """The server side as Appendix B runs it: a daemon on the HOST polls for notifications (it
+    occupies no compute unit) and accumulates what has arrived, and a client pushes again only
+    once its previous push has been consumed.  Here the daemon is a host thread that copies the
+    slot states to the host and calls the drain when a slot is full; the clients are the main
+    thread, one stream each, which poll their own column of the states before pushing.  No
+    kernel ever waits.  Gradients are small integers (every sum exact), so the result does not
+    depend on which drain took which push: nothing may be refused, lost or added twice."""
+    import threading
+    import time
+
+    N, R, K = 6_000_005, 4, 6
+    case = DeviceCase(R, [N], with_params=False)
+    L = case.layout
+    st = DeviceStaging(case)
+    L.reset_accum(case.acc_ptrs)
+    pos = (torch.arange(N, device="cuda") % 5 + 1).to(torch.float32)
+    grads = {(w, i): (pos * float(w * K + i + 1)).to(torch.bfloat16) for w in range(R) for i in range(K)}   # <= 120: exact
+    torch.cuda.synchronize()
+    nflag = R * R
+    stop, failed, drains = threading.Event(), [], [0]
+
+    def daemon():
+        try:
+            stream = torch.cuda.Stream()
+            seen = torch.empty(nflag + 1, dtype=torch.int32, pin_memory=True)
+            with torch.cuda.stream(stream):
+                while True:
+                    seen.copy_(st.flags, non_blocking=True)
+                    stream.synchronize()
+                    if bool((seen[:nflag] == 1).any()):
+                        L.stage_drain(st.bufs, st.flags, st.snap, case.acc_ptrs, stream=stream)
+                        drains[0] += 1
+                    elif stop.is_set():
+                        return
+                    else:
+                        time.sleep(0.0002)
+        except BaseException as e:          # reported by the main thread
+            failed.append(repr(e))
+
+    server = threading.Thread(target=daemon)
+    server.start()
+    try:
+        streams = [torch.cuda.Stream() for _ in range(R)]
+        mine = torch.empty(nflag + 1, dtype=torch.int32, pin_memory=True)
+        poll = torch.cuda.Stream()
+
+        def wait_until(ready, what):
+            deadline = time.time() + 60
+            while True:
+                with torch.cuda.stream(poll):
+                    mine.copy_(st.flags, non_blocking=True)
+                poll.synchronize()
+                if ready(mine[:nflag].view(R, R)):
+                    return
+                assert time.time() < deadline and not failed, f"{what}: {failed or 'timed out'}"
+                time.sleep(0.0002)
+
+        for i in range(K):
+            for w in range(R):
+                wait_until(lambda states: bool((states[:, w] == 0).all()), f"client {w} waiting for its slots")
+                L.stage_push(grads[(w, i)], st.bufs, st.flags, w, stream=streams[w])
+        for s in streams:
+            s.synchronize()
+        wait_until(lambda states: bool((states == 0).all()), "waiting for the daemon to consume everything")
+    finally:
+        stop.set()
+        server.join(timeout=60)
+    assert not failed and not server.is_alive(), failed
+    torch.cuda.synchronize()
+    flags = st.flags.cpu().numpy()
+    assert not flags[:nflag].any() and flags[nflag] == 0                      # nothing staged, nothing refused
+    total = float(sum(range(1, R * K + 1)))
+    S = case.S[0]
+    pos_h = (np.arange(N) % 5 + 1).astype(np.float32)
+    for r, a in enumerate(case.acc_host()):
+        valid = max(0, min(S, N - r * S))
+        assert np.array_equal(a[:valid], pos_h[r * S:r * S + valid] * np.float32(total)), f"owner {r}"
+    print(f"host daemon: {R * K} pushes consumed by {drains[0]} drains", flush=True)
+    case.check_guards()
+    case.close()
+
+
 def test_staging_argument_errors():
     case = DeviceCase(4, [1000], with_params=False)
     st = DeviceStaging(case)
