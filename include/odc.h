@@ -378,8 +378,9 @@ int odc_last_hip_error(void);
  *                   retrieve and reset kernels: 0 = built-in choice (two for the
  *                   read-modify-write kernels when the launch is large enough, one for reset
  *                   and for small launches), or 1, 2, 4, 8
- *   "gather_tile_xcd_block"  multi-tensor gather: tiles are handed to the 8 XCDs in blocks of this
- *                   many consecutive tiles (a power of two up to 4096; 1 = plain order)
+ *   "gather_tile_xcd_block"  multi-tensor gather: tiles are handed to the 8 XCDs in blocks of up to
+ *                   this many consecutive tiles (a power of two up to 4096, default 16; 1 = plain
+ *                   order; launches with few tiles take smaller blocks by themselves)
  *   "defaults"      with value 0: every knob back to its built-in default
  * Returns ODC_ERR_INVALID_ARG for an unknown name or a value out of range.  Results never
  * depend on the knobs.

@@ -105,7 +105,7 @@ struct Tuning {
     int tile_remap = 0;        // 1: each XCD sweeps its own contiguous eighth of the tiles
     int gather_store_sc1 = 1;  // 1: gather stores use sc1 + nt (about 3 % faster than nt on this GPU)
     int batch_rank_group = 0;  // owners per workgroup in batched accumulate/reset: 0 = auto, 1, 2, 4, 8
-    int gather_tile_xcd_block = 8;  // batched gather: tiles handed to the 8 XCDs in blocks of this many (power of two)
+    int gather_tile_xcd_block = 16;  // batched gather: tiles handed to the 8 XCDs in blocks of up to this many (power of two)
 };
 // The knobs are process-wide.  Every launcher takes ONE copy at its start (under a lock) and
 // computes grid, kernel variant and kernel arguments from that copy, so a thread that changes a

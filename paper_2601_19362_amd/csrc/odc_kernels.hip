@@ -153,8 +153,13 @@ int launch_gather_batched(const BatchTable &tb, const void *const *ptrs, int r0,
     uint16_t *out = static_cast<uint16_t *>(full);
     const int64_t chunks = (tb.full_elems + kChunkElems - 1) >> kChunkShift;
     const int64_t tiles = (chunks + kGatherChunks - 1) / kGatherChunks;
+    // Tiles go to the XCDs in blocks of consecutive tiles (knob: up to 16); a launch with few
+    // tiles takes smaller blocks, so that every XCD still gets at least eight of them and no
+    // XCD is left without work.
+    int block = t.gather_tile_xcd_block;
+    while (block > 1 && tiles < int64_t{64} * block) block >>= 1;
     int tshift = 0;
-    while ((1 << tshift) < t.gather_tile_xcd_block) ++tshift;
+    while ((1 << tshift) < block) ++tshift;
     const int64_t tgroup = int64_t{8} << tshift;
     const dim3 grid(batched_grid_x(t, (tiles + tgroup - 1) / tgroup * tgroup));
 #define ODC_GATHER_BATCHED(CAP_, BIG_)                                 \
