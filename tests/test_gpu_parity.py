@@ -118,6 +118,22 @@ def test_results_do_not_depend_on_launch_knobs(oracle, knobs):
         odc.reset_tuning()
 
 
+@pytest.mark.parametrize("rg", [2, 4, 8])
+def test_owner_groups_forced(oracle, rg):
+    """The multi-tensor kernels with 2, 4 and 8 owners per workgroup forced (the built-in choice
+    takes more than one only on large launches, which the small parity layouts never are): the
+    accumulate, reset and retrieve variants, and the two-owner staging push."""
+    try:
+        odc.tune("batch_rank_group", rg)
+        run_case(oracle, [30000, 17, 2048, 2049, 100_001], 5, [(0, 0), (4, 2)], seed=81)
+        run_case(oracle, [3, 1, 1, 2, 70, 5000, 2, 2, 129, 1], 64, [(0, 0), (63, 1)], seed=82)
+        weighted_retrieve_case(oracle, [30000, 17, 2048, 2049, 100_001], 5, seed=83, weights=[0.37, None], scale=0.25)
+        staging_case(oracle, [30000, 17, 2048, 2049, 1_000_001], 5)
+        staging_case(oracle, [5] * 70 + [100_000], 70)
+    finally:
+        odc.reset_tuning()
+
+
 def test_special_values(oracle):
     """Subnormals are kept, signed zeros and infinities follow IEEE-754, NaN stays NaN."""
     specials = np.array([0x0001, 0x0003, 0x8001, 0x007F, 0x0080, 0x8000, 0x0000, 0x7F80, 0xFF80,
