@@ -64,28 +64,13 @@ __device__ __forceinline__ void st(V *p, V v)
 // so the store is written as one instruction.  It is an ordinary vector store: the only
 // thing the compiler does not know is that it bumps the memory-operation counter, which can
 // only make a later wait longer, never too short.
-__device__ __forceinline__ void st_sc1_nt(u32x4 *p, u32x4 v)
+template <typename V>
+__device__ __forceinline__ void st_sc1_nt(V *p, V v)
 {
+    static_assert(sizeof(V) == 16 || sizeof(V) == 8, "a 16-byte or an 8-byte vector");
 #ifdef __HIP_DEVICE_COMPILE__
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
-#else
-    *p = v;
-#endif
-}
-
-__device__ __forceinline__ void st_sc1_nt(f32x4 *p, f32x4 v)
-{
-#ifdef __HIP_DEVICE_COMPILE__
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
-#else
-    *p = v;
-#endif
-}
-
-__device__ __forceinline__ void st_sc1_nt(u32x2 *p, u32x2 v)
-{
-#ifdef __HIP_DEVICE_COMPILE__
-    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+    if constexpr (sizeof(V) == 16) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 #else
     *p = v;
 #endif
